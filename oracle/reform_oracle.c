@@ -1,0 +1,316 @@
+/*
+ * reform_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, fp64 CPU statement of what the REFORM compress-and-gather hot
+ * path computes.  It exists so that tests, the smoke check and the benchmark's
+ * CPU-baseline leg have something obviously correct to compare the GPU library
+ * against.  The GPU library never includes, links or calls anything in this
+ * file, and this file includes nothing from the GPU library.
+ *
+ * Every routine is the textbook definition written out row by row: no
+ * tiling, no online softmax, no fusion.  Inputs arrive as float (bf16 and
+ * fp32 inputs widen to float exactly, so the caller's widening changes no
+ * bit); all arithmetic is double.
+ *
+ * Paper passages followed (arXiv 2506.01215):
+ *   - Sec. 3.1 "Embedding extraction with recurrent chunked forwarding":
+ *     each chunk is forwarded conditioned on the compressed KV cache of the
+ *     earlier chunks (Fig. 1 step 1, Alg. 1 ForwardChunk), then the cache is
+ *     compressed by attention-based token eviction in the manner of H2O,
+ *     retained tokens keeping their order (consecutive position ids).
+ *   - Sec. 1 ("retaining only the heavy hitters") and Sec. 4 common setup
+ *     (always-kept initial/recent tokens, 128-query observation window of
+ *     the H2O implementation).
+ *   - Sec. 3.2, the concatenation-of-normalised-heads equation, and Sec. 3.3
+ *     "Identification of significant inputs" (cosine similarity between
+ *     query and context embeddings, highest scores selected, forced first
+ *     and last tokens), App. C.6 "Similarity search".
+ *
+ * Readings taken where the paper gives no formula (each is listed in the
+ * design document of this repository):
+ *   - eviction score of key j in KV head g = sum over the G query heads of
+ *     the group and over the observing rows of the post-softmax probability
+ *     p_ij (attention mass received); raw sum, no normalisation;
+ *   - mask: every cache row is visible, chunk rows are causal with the
+ *     diagonal included;
+ *   - ties in any top selection go to the lowest index;
+ *   - cosine uses the clamp  dot / max(|e||u|, eps).
+ *
+ * Parity status: every routine below is pinned by CPU tests against brute
+ * force, closed forms, invariants and library routines (tests/test_oracle_*).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------ */
+/* One attention row, straight from the definition (Sec. 3.1, Fig. 1 step 1):
+ *   s_j   = scale * <q, k_j>           for j = 0 .. nvis-1
+ *   p_j   = exp(s_j - max s) / sum_j exp(s_j - max s)
+ *   o     = sum_j p_j v_j
+ *   lse   = max s + log(sum_j exp(s_j - max s))
+ * p (length nvis) is left in `p` for the caller.                            */
+static void attention_row(const float *q, const float *k, const float *v,
+                          int d, int nvis, double scale,
+                          double *p, double *o, double *lse)
+{
+    double m = -INFINITY;
+    for (int j = 0; j < nvis; ++j) {
+        const float *kj = k + (size_t)j * d;
+        double s = 0.0;
+        for (int c = 0; c < d; ++c) s += (double)q[c] * (double)kj[c];
+        s *= scale;
+        p[j] = s;
+        if (s > m) m = s;
+    }
+    double l = 0.0;
+    for (int j = 0; j < nvis; ++j) { p[j] = exp(p[j] - m); l += p[j]; }
+    for (int c = 0; c < d; ++c) o[c] = 0.0;
+    for (int j = 0; j < nvis; ++j) {
+        p[j] /= l;
+        const float *vj = v + (size_t)j * d;
+        for (int c = 0; c < d; ++c) o[c] += p[j] * (double)vj[c];
+    }
+    *lse = m + log(l);
+}
+
+/* Chunk attention over [cache || chunk] plus the eviction score.
+ *
+ * q      [Hq][Ct][d]     queries of the chunk
+ * k, v   [Hkv][cap][d]   rows [0,M) = retained cache, rows [M,M+Ct) = chunk
+ * out    [Hq][Ct][d]     attention output               (may be NULL)
+ * lse    [Hq][Ct]        log-sum-exp of the scaled logits (may be NULL)
+ * score  [Hkv][cap]      entries [0,M+Ct): attention mass key j received from
+ *                        the last W rows of the chunk, summed over the
+ *                        G = Hq/Hkv query heads of the group.  Overwritten
+ *                        unless accumulate != 0.        (may be NULL)
+ * Row i (0-based inside the chunk) sees keys j <= M + i.
+ * Returns 0, or -1 on a bad argument.                                       */
+int oracle_attend_score(const float *q, const float *k, const float *v,
+                        int Hq, int Hkv, int d, int M, int Ct, int cap,
+                        double scale, int W, int accumulate,
+                        double *out, double *lse, double *score)
+{
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv || d <= 0 || M < 0 || Ct <= 0 ||
+        cap < M + Ct || W < 0 || W > Ct)
+        return -1;
+    if (W == 0) W = Ct;
+    const int G = Hq / Hkv;
+    const int n = M + Ct;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int g = 0; g < Hkv; ++g) {
+        double *p = (double *)malloc(sizeof(double) * (size_t)n);
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!p || !o) { bad = 1; free(p); free(o); continue; }
+        const float *kg = k + (size_t)g * cap * d;
+        const float *vg = v + (size_t)g * cap * d;
+        double *sg = score ? score + (size_t)g * cap : NULL;
+        if (sg && !accumulate)
+            for (int j = 0; j < n; ++j) sg[j] = 0.0;
+        for (int hh = 0; hh < G; ++hh) {
+            const int h = g * G + hh;
+            for (int i = 0; i < Ct; ++i) {
+                const float *qi = q + ((size_t)h * Ct + i) * d;
+                const int nvis = M + i + 1;
+                double l;
+                attention_row(qi, kg, vg, d, nvis, scale, p, o, &l);
+                if (out)
+                    memcpy(out + ((size_t)h * Ct + i) * d, o, sizeof(double) * (size_t)d);
+                if (lse) lse[(size_t)h * Ct + i] = l;
+                if (sg && i >= Ct - W)
+                    for (int j = 0; j < nvis; ++j) sg[j] += p[j];
+            }
+        }
+        free(p); free(o);
+    }
+    return bad ? -2 : 0;
+}
+
+/* Same definition for a caller-chosen list of rows only (used to check
+ * sampled outputs at sizes where the full pass would take hours).
+ * rows_h[r], rows_i[r] name query head and chunk row of sample r.
+ * out [nrows][d], lse [nrows].                                              */
+int oracle_attend_rows(const float *q, const float *k, const float *v,
+                       int Hq, int Hkv, int d, int M, int Ct, int cap,
+                       double scale, const int32_t *rows_h, const int32_t *rows_i,
+                       int nrows, double *out, double *lse)
+{
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv || d <= 0 || M < 0 || Ct <= 0 || cap < M + Ct)
+        return -1;
+    const int G = Hq / Hkv;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < nrows; ++r) {
+        const int h = rows_h[r], i = rows_i[r];
+        if (h < 0 || h >= Hq || i < 0 || i >= Ct) { bad = 1; continue; }
+        const int g = h / G;
+        const int nvis = M + i + 1;
+        double *p = (double *)malloc(sizeof(double) * (size_t)nvis);
+        if (!p) { bad = 1; continue; }
+        attention_row(q + ((size_t)h * Ct + i) * d, k + (size_t)g * cap * d,
+                      v + (size_t)g * cap * d, d, nvis, scale, p,
+                      out + (size_t)r * d, lse + r);
+        free(p);
+    }
+    return bad ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Selection of the `keep` largest of x[0..n), ties to the lowest index.
+ * Definition: sort indices by (value descending, index ascending), take the
+ * first `keep`, then list them in ascending index order.                    */
+typedef struct { double val; int32_t idx; } oracle_pair;
+
+static int cmp_val_desc_idx_asc(const void *a, const void *b)
+{
+    const oracle_pair *x = (const oracle_pair *)a, *y = (const oracle_pair *)b;
+    if (x->val > y->val) return -1;
+    if (x->val < y->val) return 1;
+    return (x->idx > y->idx) - (x->idx < y->idx);
+}
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* out_idx[keep], ascending.  Returns 0 or -1.                               */
+int oracle_topk_lowest_index(const double *x, int64_t n, int64_t keep, int32_t *out_idx)
+{
+    if (n < 0 || keep < 0 || keep > n) return -1;
+    oracle_pair *a = (oracle_pair *)malloc(sizeof(oracle_pair) * (size_t)(n ? n : 1));
+    if (!a) return -2;
+    for (int64_t j = 0; j < n; ++j) { a[j].val = x[j]; a[j].idx = (int32_t)j; }
+    qsort(a, (size_t)n, sizeof(oracle_pair), cmp_val_desc_idx_asc);
+    for (int64_t r = 0; r < keep; ++r) out_idx[r] = a[r].idx;
+    qsort(out_idx, (size_t)keep, sizeof(int32_t), cmp_i32);
+    free(a);
+    return 0;
+}
+
+/* Heavy-hitter retention for one KV head (Sec. 3.1; Sec. 1; Sec. 4 setup):
+ * among n = M + Ct candidate slots keep the B with the largest score; the
+ * first n_sink and the last n_recent slots are always kept and count inside
+ * B.  If n <= B everything is kept.  kept[min(n,B)] ascending.
+ * Returns the number kept, or -1 on a bad argument.                         */
+int oracle_evict_select(const double *score, int n, int B, int n_sink, int n_recent,
+                        int32_t *kept)
+{
+    if (n < 0 || B < 0 || n_sink < 0 || n_recent < 0 || n_sink + n_recent > B) return -1;
+    if (n <= B) {
+        for (int j = 0; j < n; ++j) kept[j] = j;
+        return n;
+    }
+    double *key = (double *)malloc(sizeof(double) * (size_t)n);
+    if (!key) return -2;
+    for (int j = 0; j < n; ++j)
+        key[j] = (j < n_sink || j >= n - n_recent) ? INFINITY : score[j];
+    int rc = oracle_topk_lowest_index(key, n, B, kept);
+    free(key);
+    return rc ? rc : B;
+}
+
+/* Order-preserving compaction (Sec. 3.1: retained tokens get consecutive
+ * position ids): row r of the result is row kept[r] of the input, for
+ * K, V (row length d), score and pos of one KV head.  Goes through a
+ * temporary, never in place.  Any of k, v, score, pos may be NULL.          */
+int oracle_compact_rows(float *k, float *v, double *score, int32_t *pos,
+                        int d, const int32_t *kept, int n_kept)
+{
+    if (n_kept < 0 || d <= 0) return -1;
+    size_t rows = (size_t)(n_kept ? n_kept : 1);
+    float *tk = (float *)malloc(sizeof(float) * rows * d);
+    float *tv = (float *)malloc(sizeof(float) * rows * d);
+    double *ts = (double *)malloc(sizeof(double) * rows);
+    int32_t *tp = (int32_t *)malloc(sizeof(int32_t) * rows);
+    if (!tk || !tv || !ts || !tp) { free(tk); free(tv); free(ts); free(tp); return -2; }
+    for (int r = 0; r < n_kept; ++r) {
+        const size_t s = (size_t)kept[r];
+        if (k) memcpy(tk + (size_t)r * d, k + s * d, sizeof(float) * (size_t)d);
+        if (v) memcpy(tv + (size_t)r * d, v + s * d, sizeof(float) * (size_t)d);
+        if (score) ts[r] = score[s];
+        if (pos) tp[r] = pos[s];
+    }
+    if (k) memcpy(k, tk, sizeof(float) * (size_t)n_kept * d);
+    if (v) memcpy(v, tv, sizeof(float) * (size_t)n_kept * d);
+    if (score) memcpy(score, ts, sizeof(double) * (size_t)n_kept);
+    if (pos) memcpy(pos, tp, sizeof(int32_t) * (size_t)n_kept);
+    free(tk); free(tv); free(ts); free(tp);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Cosine similarity of every context embedding with every query embedding
+ * (Sec. 3.3; App. C.6):  sim[q][t] = <e_t,u_q> / max(|e_t| |u_q|, eps).
+ * emb [N][D], qry [nq][D], sim [nq][N].                                     */
+int oracle_cosine(const float *emb, const float *qry, int64_t N, int D, int nq,
+                  double eps, double *sim)
+{
+    if (N < 0 || D <= 0 || nq <= 0) return -1;
+    for (int qi = 0; qi < nq; ++qi) {
+        const float *u = qry + (size_t)qi * D;
+        double un = 0.0;
+        for (int c = 0; c < D; ++c) un += (double)u[c] * (double)u[c];
+        un = sqrt(un);
+#pragma omp parallel for schedule(static)
+        for (int64_t t = 0; t < N; ++t) {
+            const float *e = emb + (size_t)t * D;
+            double dot = 0.0, en = 0.0;
+            for (int c = 0; c < D; ++c) {
+                dot += (double)e[c] * (double)u[c];
+                en += (double)e[c] * (double)e[c];
+            }
+            double den = sqrt(en) * un;
+            if (den < eps) den = eps;
+            sim[(size_t)qi * N + t] = dot / den;
+        }
+    }
+    return 0;
+}
+
+/* Union of the per-query top-k lists, each index widened by +-radius
+ * (clipped to [0,N)), plus the forced first n_head and last n_tail rows
+ * (Sec. 3.3: the first and last tokens are always kept; the neighbourhood
+ * keeps gathered spans contiguous).  Output ascending, no duplicates.
+ * topk [nq][k];  out has room for N entries.  Returns the count or -1.      */
+int64_t oracle_union_dilate(const int32_t *topk, int nq, int64_t k, int64_t N,
+                            int radius, int64_t n_head, int64_t n_tail, int32_t *out)
+{
+    if (nq < 0 || k < 0 || N < 0 || radius < 0 || n_head < 0 || n_tail < 0) return -1;
+    size_t total = (size_t)nq * (size_t)k * (size_t)(2 * radius + 1) +
+                   (size_t)n_head + (size_t)n_tail;
+    int32_t *all = (int32_t *)malloc(sizeof(int32_t) * (total ? total : 1));
+    if (!all) return -2;
+    size_t m = 0;
+    for (int qi = 0; qi < nq; ++qi)
+        for (int64_t r = 0; r < k; ++r) {
+            const int64_t t = topk[(size_t)qi * k + r];
+            for (int64_t dlt = -radius; dlt <= radius; ++dlt) {
+                const int64_t u = t + dlt;
+                if (u >= 0 && u < N) all[m++] = (int32_t)u;
+            }
+        }
+    for (int64_t t = 0; t < n_head && t < N; ++t) all[m++] = (int32_t)t;
+    for (int64_t t = 0; t < n_tail && t < N; ++t) all[m++] = (int32_t)(N - 1 - t);
+    qsort(all, m, sizeof(int32_t), cmp_i32);
+    int64_t cnt = 0;
+    for (size_t a = 0; a < m; ++a)
+        if (a == 0 || all[a] != all[a - 1]) out[cnt++] = all[a];
+    free(all);
+    return cnt;
+}
