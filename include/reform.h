@@ -1,0 +1,184 @@
+/*
+ * reform.h -- C ABI of the MI355X (gfx950) REFORM compress-and-gather hot path.
+ *
+ * Three calls, named after the steps of the method (arXiv 2506.01215):
+ *
+ *   reform_chunk_attend_score   Alg. 1 `layer.Forward(hs, cache)`, attention part: one chunk of
+ *                               queries attends causally over [compressed KV cache || chunk KV]
+ *                               (Sec. 3.1, Fig. 1 step 1) and, in the same call, produces the
+ *                               attention-based eviction score of every key (Sec. 3.1 "attention-
+ *                               based token eviction following H2O"; Sec. 5 names fusing this
+ *                               score into the attention kernel as the open efficiency item).
+ *   reform_evict_topk_compact   Alg. 1 `Compress(cache)`: keep the heavy hitters up to the budget
+ *                               and re-pack the cache so retained tokens are consecutive
+ *                               (Sec. 3.1, Sec. 1, Sec. 4 common setup).
+ *   reform_gather_topk          Alg. 1 `GatherRelevant(input, emb)`: cosine similarity between
+ *                               query embeddings and every context embedding, highest scores
+ *                               selected, neighbourhood kept contiguous (Sec. 3.3, App. C.6).
+ *
+ * Conventions common to all calls
+ *   - Every data pointer is a DEVICE pointer (HIP global memory) owned by the caller.  The
+ *     library never allocates, frees or keeps a pointer; scratch comes in through `workspace`,
+ *     whose size the matching *_workspace() query returns (bytes; 256-byte aligned base needed).
+ *   - Descriptors are HOST structs; `struct_size` must be sizeof() of the struct.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = the default stream)
+ *     and the call returns without synchronising.
+ *   - Arguments are validated on the host before anything is launched.  On any status other
+ *     than REFORM_OK nothing was launched and the outputs are unchanged, except
+ *     REFORM_ERR_RUNTIME (a HIP launch failed part-way): outputs are then undefined.
+ *   - No C++ type, exception or torch object crosses this boundary.
+ *   - Calls on different streams may overlap if their buffers (workspace included) are disjoint.
+ *   - bf16 storage is the upper 16 bits of an IEEE fp32; conversions round to nearest even.
+ */
+#ifndef REFORM_H
+#define REFORM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    REFORM_OK = 0,
+    REFORM_ERR_INVALID_ARG = 1,   /* null pointer, bad shape, wrong struct_size, ...          */
+    REFORM_ERR_UNSUPPORTED = 2,   /* well-formed but outside what the kernels implement       */
+    REFORM_ERR_WORKSPACE = 3,     /* workspace missing, misaligned or too small               */
+    REFORM_ERR_RUNTIME = 4        /* a HIP call failed                                         */
+} reform_status;
+
+typedef enum { REFORM_F32 = 0, REFORM_BF16 = 1 } reform_dtype;
+
+/* ------------------------------------------------------------------------------------------- */
+/* reform_chunk_attend_score
+ *
+ * For query head h (KV head g = h / G, G = n_q_heads / n_kv_heads) and chunk row i:
+ *     s_ij   = scale * <q_hi, k_gj>,  j in [0, cache_len + i]     (cache rows all visible, chunk
+ *                                                                 rows causal, diagonal included)
+ *     p_ij   = softmax_j(s_ij)
+ *     out_hi = sum_j p_ij v_gj
+ *     lse_hi = log sum_j exp(s_ij)
+ *     score_gj (+)= sum_{h in group g} sum_{i >= chunk_len - W} p_ij      (attention mass key j
+ *                 received from the last W = obs_window rows; Sec. 4 setup mentions W = 128 for
+ *                 the H2O baseline, the chunk's whole length is the default)
+ *
+ * Layouts (element = dtype):
+ *     q      [n_q_heads][chunk_len][head_dim]   head stride / row stride given in elements,
+ *                                               head_dim contiguous, 16-byte aligned rows
+ *     k, v   [n_kv_heads][capacity][head_dim]   contiguous; rows [0,cache_len) = retained cache,
+ *                                               rows [cache_len, cache_len+chunk_len) = this
+ *                                               chunk (the caller writes them there); rows
+ *                                               beyond are never read
+ *     out    like q, with its own strides, dtype as the inputs
+ *     lse    [n_q_heads][chunk_len] fp32, may be NULL
+ *     score  [n_kv_heads][capacity] fp32, entries [0, cache_len+chunk_len) written (added to when
+ *            accumulate != 0), the rest untouched; may be NULL (attention only)
+ * Arithmetic: products and sums in fp32; for bf16 the probabilities fed to the P.V product are
+ * rounded to bf16, the score sums the unrounded fp32 probabilities.  Results are bitwise
+ * reproducible run to run (no floating-point atomics); two cache rows holding bit-identical
+ * keys receive bit-identical scores.
+ * Supported: REFORM_BF16 with head_dim 64 or 128; REFORM_F32 with head_dim % 4 == 0, <= 256.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  dtype;                          /* reform_dtype                                   */
+    int32_t  n_q_heads, n_kv_heads, head_dim;
+    int32_t  cache_len, chunk_len, capacity; /* M >= 0, C_t >= 1, capacity >= M + C_t          */
+    int64_t  q_head_stride, q_row_stride;    /* elements                                       */
+    int64_t  o_head_stride, o_row_stride;    /* elements                                       */
+    float    scale;                          /* > 0, finite; 1/sqrt(head_dim) in the paper's models */
+    int32_t  obs_window;                     /* W in [1, chunk_len]; 0 means chunk_len         */
+    int32_t  accumulate;                     /* 0: score = ..., 1: score += ...                */
+} reform_attn_desc;
+
+size_t reform_chunk_attend_score_workspace(const reform_attn_desc *desc);
+
+reform_status reform_chunk_attend_score(const reform_attn_desc *desc,
+                                        const void *q, const void *k, const void *v,
+                                        void *out, float *lse, float *score,
+                                        void *workspace, size_t workspace_bytes,
+                                        void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------- */
+/* reform_evict_topk_compact
+ *
+ * Per KV head, among the n_valid = M + C_t candidate slots keep the `budget` slots with the
+ * largest score (ties: the lowest slot index wins); the first n_sink and the last n_recent slots
+ * are always kept and count inside the budget (Sec. 4 setup keeps the initial and recent 256
+ * tokens).  Then row r of the cache becomes old row kept_idx[r] for r < new_len, in ascending
+ * slot order, for k, v, score and pos alike -- in place.  new_len = min(n_valid, budget); it is
+ * a function of the descriptor, nothing is read back.  If n_valid <= budget nothing moves.
+ *
+ *     k, v     [n_kv_heads][capacity][head_dim], in/out; rows >= new_len keep stale content
+ *     score    [n_kv_heads][capacity] fp32, in/out; must be finite (no NaN/Inf)
+ *     pos      [n_kv_heads][capacity] int32 token ids travelling with the rows, in/out, may be NULL
+ *     kept_idx [n_kv_heads][budget] int32 out (first new_len entries per head), may be NULL
+ * Supported: head_dim * sizeof(element) must be a multiple of 16; capacity < 2^31.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  dtype;
+    int32_t  n_kv_heads, head_dim;
+    int32_t  n_valid, budget, capacity;
+    int32_t  n_sink, n_recent;               /* n_sink + n_recent <= budget                    */
+} reform_evict_desc;
+
+size_t reform_evict_topk_compact_workspace(const reform_evict_desc *desc);
+
+reform_status reform_evict_topk_compact(const reform_evict_desc *desc,
+                                        void *k, void *v, float *score,
+                                        int32_t *pos, int32_t *kept_idx,
+                                        void *workspace, size_t workspace_bytes,
+                                        void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------- */
+/* reform_gather_topk
+ *
+ *     sim_qt   = <e_t, u_q> / max(|e_t| |u_q|, eps)              (Sec. 3.3, App. C.6)
+ *     topk_q   = the k indices t with the largest sim_qt, ties to the lowest t, ascending
+ *     union    = sorted unique { t + dlt : t in any topk_q, |dlt| <= radius, 0 <= t+dlt < n_ctx }
+ *                united with the first n_head_keep and last n_tail_keep rows (Sec. 3.3 keeps
+ *                the first and last tokens and widens hits to their neighbourhood)
+ *
+ *     emb         [n_ctx][dim], contiguous, dtype
+ *     qry         [n_query][dim], contiguous, dtype
+ *     topk_idx    [n_query][k] int32 out
+ *     topk_score  [n_query][k] fp32 out (sim of the selected rows), may be NULL
+ *     union_idx   [n_ctx] int32 out (first union_count entries), may be NULL (then no union)
+ *     union_count one int32 in device memory, out, required iff union_idx != NULL
+ * Supported: n_ctx < 2^31; dim % 8 == 0; any n_query >= 1 (processed 16 at a time).
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  dtype;
+    int64_t  n_ctx;
+    int32_t  dim, n_query, k;                /* 1 <= k <= n_ctx                                */
+    int32_t  radius, n_head_keep, n_tail_keep;
+    float    eps;                            /* > 0; 1e-8 in the tests                         */
+} reform_gather_desc;
+
+size_t reform_gather_topk_workspace(const reform_gather_desc *desc);
+
+reform_status reform_gather_topk(const reform_gather_desc *desc,
+                                 const void *emb, const void *qry,
+                                 int32_t *topk_idx, float *topk_score,
+                                 int32_t *union_idx, int32_t *union_count,
+                                 void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
+
+/* Intermediate of reform_gather_topk, exposed for checking: only the similarity matrix,
+ * sim [n_query][n_ctx] fp32 (device, out).  Same descriptor, k/radius/keeps ignored.           */
+reform_status reform_gather_similarity(const reform_gather_desc *desc,
+                                       const void *emb, const void *qry, float *sim,
+                                       void *hip_stream);
+
+const char *reform_status_string(reform_status status);
+
+/* Library version, major*10000 + minor*100 + patch.                                            */
+int32_t reform_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REFORM_H */

@@ -1,8 +1,246 @@
-# placeholder replaced below
+"""Thin ctypes binding of libreform_hip.so (the C ABI declared in include/reform.h).
+
+Argument marshalling only: torch tensors supply device memory and the current HIP stream;
+every step of the path runs in the library's kernels.  There is no fallback: if the shared
+library is missing or a call returns a non-OK status, a ReformError is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libreform_hip.so")
+_LIB = None
+
+REFORM_F32, REFORM_BF16 = 0, 1
+STATUS = {0: "REFORM_OK", 1: "REFORM_ERR_INVALID_ARG", 2: "REFORM_ERR_UNSUPPORTED",
+          3: "REFORM_ERR_WORKSPACE", 4: "REFORM_ERR_RUNTIME"}
+
+EXPORTED = [
+    "reform_chunk_attend_score_workspace", "reform_chunk_attend_score",
+    "reform_evict_topk_compact_workspace", "reform_evict_topk_compact",
+    "reform_gather_topk_workspace", "reform_gather_topk", "reform_gather_similarity",
+    "reform_status_string", "reform_version",
+]
+
+
 class ReformError(RuntimeError):
-    pass
-def load_library(): raise ReformError("not built")
-def library_path(): return ""
-def reform_chunk_attend_score(*a, **k): raise ReformError("not built")
-def reform_evict_topk_compact(*a, **k): raise ReformError("not built")
-def reform_gather_topk(*a, **k): raise ReformError("not built")
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: {STATUS.get(int(status), status)}")
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32),
+                ("cache_len", ctypes.c_int32), ("chunk_len", ctypes.c_int32),
+                ("capacity", ctypes.c_int32),
+                ("q_head_stride", ctypes.c_int64), ("q_row_stride", ctypes.c_int64),
+                ("o_head_stride", ctypes.c_int64), ("o_row_stride", ctypes.c_int64),
+                ("scale", ctypes.c_float), ("obs_window", ctypes.c_int32),
+                ("accumulate", ctypes.c_int32)]
+
+
+class EvictDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("n_valid", ctypes.c_int32), ("budget", ctypes.c_int32),
+                ("capacity", ctypes.c_int32),
+                ("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32)]
+
+
+class GatherDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("n_ctx", ctypes.c_int64),
+                ("dim", ctypes.c_int32), ("n_query", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("radius", ctypes.c_int32), ("n_head_keep", ctypes.c_int32),
+                ("n_tail_keep", ctypes.c_int32), ("eps", ctypes.c_float)]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libreform_hip.so (built by paper_2506_01215_amd.build); raises if it is absent."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} not found: build it with `python -m paper_2506_01215_amd.build`"
+                           " (there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    lib.reform_chunk_attend_score_workspace.restype = sz
+    lib.reform_chunk_attend_score_workspace.argtypes = [ctypes.POINTER(AttnDesc)]
+    lib.reform_chunk_attend_score.restype = ctypes.c_int
+    lib.reform_chunk_attend_score.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.reform_evict_topk_compact_workspace.restype = sz
+    lib.reform_evict_topk_compact_workspace.argtypes = [ctypes.POINTER(EvictDesc)]
+    lib.reform_evict_topk_compact.restype = ctypes.c_int
+    lib.reform_evict_topk_compact.argtypes = [ctypes.POINTER(EvictDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.reform_gather_topk_workspace.restype = sz
+    lib.reform_gather_topk_workspace.argtypes = [ctypes.POINTER(GatherDesc)]
+    lib.reform_gather_topk.restype = ctypes.c_int
+    lib.reform_gather_topk.argtypes = [ctypes.POINTER(GatherDesc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.reform_gather_similarity.restype = ctypes.c_int
+    lib.reform_gather_similarity.argtypes = [ctypes.POINTER(GatherDesc), vp, vp, vp, vp]
+    lib.reform_status_string.restype = ctypes.c_char_p
+    lib.reform_status_string.argtypes = [ctypes.c_int]
+    lib.reform_version.restype = ctypes.c_int32
+    _LIB = lib
+    return lib
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return REFORM_BF16
+    if t.dtype == torch.float32:
+        return REFORM_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _workspace(nbytes, device, workspace):
+    if nbytes == 0:
+        return None
+    if workspace is None:
+        workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    off = (-workspace.data_ptr()) % 256
+    ws = workspace[off:]
+    return ws
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise ReformError(rc, where)
+
+
+# ------------------------------------------------------------------------------------------
+def attn_desc(q, k, out, cache_len, scale, obs_window=0, accumulate=False):
+    Hq, Ct, d = q.shape
+    Hkv, cap, d2 = k.shape
+    assert d2 == d and q.stride(2) == 1 and out.stride(2) == 1
+    return AttnDesc(ctypes.sizeof(AttnDesc), _dtype_code(q), Hq, Hkv, d, int(cache_len), Ct, cap,
+                    q.stride(0), q.stride(1), out.stride(0), out.stride(1),
+                    float(scale), int(obs_window), int(bool(accumulate)))
+
+
+def reform_chunk_attend_score(q, k, v, cache_len, scale, obs_window=0, accumulate=False,
+                              out=None, lse=None, score=None, want_score=True,
+                              workspace=None, stream=None):
+    """q [Hq,Ct,d]; k,v [Hkv,cap,d] (rows [0,M) cache, [M,M+Ct) chunk).  Returns (out, lse, score)."""
+    lib = load_library()
+    assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+    if out is None:
+        out = torch.empty_like(q, memory_format=torch.contiguous_format)
+    if lse is None:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    if score is None and want_score:
+        if accumulate:
+            raise ValueError("accumulate needs the previous score tensor")
+        score = torch.zeros(k.shape[:2], dtype=torch.float32, device=q.device)
+    desc = attn_desc(q, k, out, cache_len, scale, obs_window, accumulate)
+    need = lib.reform_chunk_attend_score_workspace(ctypes.byref(desc))
+    ws = _workspace(need, q.device, workspace)
+    rc = lib.reform_chunk_attend_score(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                       _ptr(lse), _ptr(score), _ptr(ws),
+                                       0 if ws is None else ws.numel(), _stream(stream))
+    _check(rc, "reform_chunk_attend_score")
+    return out, lse, score
+
+
+def evict_desc(k, n_valid, budget, n_sink=0, n_recent=0):
+    Hkv, cap, d = k.shape
+    return EvictDesc(ctypes.sizeof(EvictDesc), _dtype_code(k), Hkv, d, int(n_valid), int(budget), cap,
+                     int(n_sink), int(n_recent))
+
+
+def reform_evict_topk_compact(k, v, score, n_valid, budget, n_sink=0, n_recent=0, pos=None,
+                              kept_idx=None, workspace=None, stream=None):
+    """In-place retention + compaction.  Returns new_len = min(n_valid, budget)."""
+    lib = load_library()
+    assert k.is_contiguous() and v.is_contiguous() and score.is_contiguous()
+    assert score.dtype == torch.float32 and score.shape == k.shape[:2]
+    if pos is not None:
+        assert pos.dtype == torch.int32 and pos.is_contiguous() and pos.shape == k.shape[:2]
+    if kept_idx is not None:
+        assert kept_idx.dtype == torch.int32 and kept_idx.is_contiguous()
+        assert kept_idx.shape == (k.shape[0], budget)
+    desc = evict_desc(k, n_valid, budget, n_sink, n_recent)
+    need = lib.reform_evict_topk_compact_workspace(ctypes.byref(desc))
+    ws = _workspace(need, k.device, workspace)
+    rc = lib.reform_evict_topk_compact(ctypes.byref(desc), _ptr(k), _ptr(v), _ptr(score), _ptr(pos),
+                                       _ptr(kept_idx), _ptr(ws), 0 if ws is None else ws.numel(),
+                                       _stream(stream))
+    _check(rc, "reform_evict_topk_compact")
+    return min(int(n_valid), int(budget))
+
+
+def gather_desc(emb, qry, k, radius=0, n_head_keep=0, n_tail_keep=0, eps=1e-8):
+    N, D = emb.shape
+    nq, D2 = qry.shape
+    assert D == D2 and emb.dtype == qry.dtype
+    return GatherDesc(ctypes.sizeof(GatherDesc), _dtype_code(emb), N, D, nq, int(k), int(radius),
+                      int(n_head_keep), int(n_tail_keep), float(eps))
+
+
+def reform_gather_topk(emb, qry, k, radius=0, n_head_keep=0, n_tail_keep=0, eps=1e-8,
+                       want_union=True, topk_idx=None, topk_score=None, union_idx=None,
+                       union_count=None, workspace=None, stream=None):
+    """Returns (topk_idx [nq,k] i32, topk_score [nq,k] f32, union_idx [N] i32 or None, union_count)."""
+    lib = load_library()
+    assert emb.is_contiguous() and qry.is_contiguous()
+    N, nq = emb.shape[0], qry.shape[0]
+    dev = emb.device
+    if topk_idx is None:
+        topk_idx = torch.empty((nq, k), dtype=torch.int32, device=dev)
+    if topk_score is None:
+        topk_score = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    if want_union:
+        if union_idx is None:
+            union_idx = torch.empty((N,), dtype=torch.int32, device=dev)
+        if union_count is None:
+            union_count = torch.zeros((1,), dtype=torch.int32, device=dev)
+    desc = gather_desc(emb, qry, k, radius, n_head_keep, n_tail_keep, eps)
+    need = lib.reform_gather_topk_workspace(ctypes.byref(desc))
+    ws = _workspace(need, dev, workspace)
+    rc = lib.reform_gather_topk(ctypes.byref(desc), _ptr(emb), _ptr(qry), _ptr(topk_idx),
+                                _ptr(topk_score), _ptr(union_idx), _ptr(union_count), _ptr(ws),
+                                0 if ws is None else ws.numel(), _stream(stream))
+    _check(rc, "reform_gather_topk")
+    return topk_idx, topk_score, union_idx, union_count
+
+
+def reform_gather_similarity(emb, qry, eps=1e-8, sim=None, stream=None):
+    lib = load_library()
+    assert emb.is_contiguous() and qry.is_contiguous()
+    if sim is None:
+        sim = torch.empty((qry.shape[0], emb.shape[0]), dtype=torch.float32, device=emb.device)
+    desc = gather_desc(emb, qry, 1, eps=eps)
+    rc = lib.reform_gather_similarity(ctypes.byref(desc), _ptr(emb), _ptr(qry), _ptr(sim), _stream(stream))
+    _check(rc, "reform_gather_similarity")
+    return sim
+
+
+def attend_workspace_bytes(desc):
+    return load_library().reform_chunk_attend_score_workspace(ctypes.byref(desc))
+
+
+def evict_workspace_bytes(desc):
+    return load_library().reform_evict_topk_compact_workspace(ctypes.byref(desc))
+
+
+def gather_workspace_bytes(desc):
+    return load_library().reform_gather_topk_workspace(ctypes.byref(desc))

@@ -1,0 +1,106 @@
+// Shared device helpers and launch-parameter structs of the gfx950 kernels.
+// Nothing here is shared with the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace reform {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16;
+
+constexpr int kWave = 64;
+
+struct AttnParams {
+    const void *q, *k, *v;
+    void *out;
+    float *lse;      // never null inside the kernels (caller's buffer or workspace)
+    float *score;    // may be null for the forward kernel
+    int Hq, Hkv, G, D;
+    int M, Ct, cap, n;
+    long q_hs, q_rs, o_hs, o_rs;
+    float scale;
+    int W;           // resolved observation window, 1..Ct
+    int accumulate;
+    int gp;          // query heads of one group that share a workgroup (1, 2 or 4)
+    int n_row_blocks;
+};
+
+struct EvictParams {
+    void *k, *v;
+    float *score;
+    int32_t *pos;
+    int32_t *kept;      // [Hkv][B]
+    void *stage_k, *stage_v;   // [Hkv][B][row_bytes]
+    int Hkv, n, B, cap, n_sink, n_recent;
+    int row_bytes;      // head_dim * sizeof(element), multiple of 16
+};
+
+struct GatherParams {
+    const void *emb, *qry;
+    float *sim;          // [nq][N]
+    int32_t *topk_idx;   // [nq][k]
+    float *topk_score;   // nullable
+    int32_t *union_idx;  // nullable
+    int32_t *union_count;
+    // workspace pieces
+    int *hist;           // [nq][3][2048]
+    uint32_t *sel_prefix;   // [nq]
+    int *sel_krem;       // [nq]
+    int *blk_cnt;        // [nq][nblk][2]   (gt, eq)
+    uint32_t *bitmap;    // [nwords]
+    int *word_cnt;       // [n_union_blocks]
+    long N;
+    int D, nq, k, radius, n_head, n_tail;
+    int nblk;            // selection blocks per query
+    int nwords;          // bitmap words
+    float eps;
+    int q0, nq_grp;      // query group handled by this similarity launch
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(u16 b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
+__device__ __forceinline__ u16 f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u16)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (u16)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 v = {lo, hi};
+    bf16x2 r = __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32 on gfx950 (RNE)
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+
+// Monotone map float -> uint32: a > b  <=>  key(a) > key(b) (finite values; -0 and +0 map alike).
+__device__ __forceinline__ uint32_t ordered_key(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+}  // namespace reform

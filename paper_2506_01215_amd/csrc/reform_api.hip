@@ -1,0 +1,271 @@
+// C ABI of the library (see include/reform.h): host-side validation, workspace carving and
+// kernel launches.  Nothing here allocates device memory or synchronises.
+#include "../../include/reform.h"
+#include "common.h"
+
+#include <cmath>
+#include <cstring>
+
+namespace reform {
+hipError_t attend_bf16_forward(const AttnParams &p, hipStream_t st);
+hipError_t attend_bf16_score(const AttnParams &p, hipStream_t st);
+hipError_t attend_f32_forward(const AttnParams &p, hipStream_t st);
+hipError_t attend_f32_score(const AttnParams &p, hipStream_t st);
+
+hipError_t evict_run(const EvictParams &p, hipStream_t st);
+hipError_t evict_fill_identity(int32_t *kept, int Hkv, int B, int n, hipStream_t st);
+
+hipError_t gather_similarity(GatherParams p, int dtype_is_bf16, hipStream_t st);
+hipError_t gather_select_union(GatherParams p, hipStream_t st);
+}  // namespace reform
+
+using namespace reform;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+inline size_t elt_size(int dtype) { return dtype == REFORM_BF16 ? 2 : 4; }
+
+reform_status check_attn(const reform_attn_desc *d)
+{
+    if (!d || d->struct_size != sizeof(reform_attn_desc)) return REFORM_ERR_INVALID_ARG;
+    if (d->dtype != REFORM_F32 && d->dtype != REFORM_BF16) return REFORM_ERR_INVALID_ARG;
+    if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->n_q_heads % d->n_kv_heads) return REFORM_ERR_INVALID_ARG;
+    if (d->head_dim <= 0 || d->cache_len < 0 || d->chunk_len <= 0) return REFORM_ERR_INVALID_ARG;
+    if ((int64_t)d->cache_len + d->chunk_len > d->capacity) return REFORM_ERR_INVALID_ARG;
+    if (!(d->scale > 0.f) || !std::isfinite(d->scale)) return REFORM_ERR_INVALID_ARG;
+    if (d->obs_window < 0 || d->obs_window > d->chunk_len) return REFORM_ERR_INVALID_ARG;
+    if (d->accumulate != 0 && d->accumulate != 1) return REFORM_ERR_INVALID_ARG;
+    if (d->q_row_stride < d->head_dim || d->o_row_stride < d->head_dim) return REFORM_ERR_INVALID_ARG;
+    if (d->q_head_stride < 0 || d->o_head_stride < 0) return REFORM_ERR_INVALID_ARG;
+    const int per16 = (int)(16 / elt_size(d->dtype));
+    if (d->q_row_stride % per16 || d->q_head_stride % per16 || d->o_row_stride % per16 ||
+        d->o_head_stride % per16)
+        return REFORM_ERR_INVALID_ARG;
+    if (d->dtype == REFORM_BF16) {
+        if (d->head_dim != 64 && d->head_dim != 128) return REFORM_ERR_UNSUPPORTED;
+    } else {
+        if (d->head_dim % 4 || d->head_dim > 256) return REFORM_ERR_UNSUPPORTED;
+    }
+    if ((int64_t)d->n_q_heads * d->chunk_len >= (1ll << 31) ||
+        (int64_t)d->n_kv_heads * ((int64_t)d->cache_len + d->chunk_len) >= (1ll << 31))
+        return REFORM_ERR_UNSUPPORTED;
+    return REFORM_OK;
+}
+
+reform_status check_evict(const reform_evict_desc *d)
+{
+    if (!d || d->struct_size != sizeof(reform_evict_desc)) return REFORM_ERR_INVALID_ARG;
+    if (d->dtype != REFORM_F32 && d->dtype != REFORM_BF16) return REFORM_ERR_INVALID_ARG;
+    if (d->n_kv_heads <= 0 || d->head_dim <= 0) return REFORM_ERR_INVALID_ARG;
+    if (d->n_valid < 0 || d->budget <= 0 || d->n_valid > d->capacity) return REFORM_ERR_INVALID_ARG;
+    if (d->n_sink < 0 || d->n_recent < 0 || (int64_t)d->n_sink + d->n_recent > d->budget)
+        return REFORM_ERR_INVALID_ARG;
+    if ((d->head_dim * elt_size(d->dtype)) % 16) return REFORM_ERR_UNSUPPORTED;
+    if (d->n_kv_heads > 65535) return REFORM_ERR_UNSUPPORTED;
+    return REFORM_OK;
+}
+
+reform_status check_gather(const reform_gather_desc *d)
+{
+    if (!d || d->struct_size != sizeof(reform_gather_desc)) return REFORM_ERR_INVALID_ARG;
+    if (d->dtype != REFORM_F32 && d->dtype != REFORM_BF16) return REFORM_ERR_INVALID_ARG;
+    if (d->n_ctx <= 0 || d->dim <= 0 || d->n_query <= 0) return REFORM_ERR_INVALID_ARG;
+    if (d->k <= 0 || d->k > d->n_ctx) return REFORM_ERR_INVALID_ARG;
+    if (d->radius < 0 || d->n_head_keep < 0 || d->n_tail_keep < 0) return REFORM_ERR_INVALID_ARG;
+    if (!(d->eps > 0.f) || !std::isfinite(d->eps)) return REFORM_ERR_INVALID_ARG;
+    if (d->n_ctx >= (1ll << 31)) return REFORM_ERR_UNSUPPORTED;
+    if (d->dim % 8) return REFORM_ERR_UNSUPPORTED;
+    if (d->n_query > 65535) return REFORM_ERR_UNSUPPORTED;
+    const int grp = d->n_query < 16 ? d->n_query : 16;
+    if ((size_t)grp * d->dim * 4 > 150 * 1024 && !(d->dtype == REFORM_BF16 && d->dim % 32 == 0 &&
+                                                     (size_t)16 * (d->dim + 8) * 2 <= 150 * 1024))
+        return REFORM_ERR_UNSUPPORTED;
+    return REFORM_OK;
+}
+
+struct GatherLayout {
+    size_t sim, hist, prefix, krem, blk, bitmap, words, total;
+    int nblk, nwords, nublk;
+};
+
+GatherLayout gather_layout(const reform_gather_desc *d)
+{
+    GatherLayout L;
+    L.nblk = (int)((d->n_ctx + 4095) / 4096);
+    L.nwords = (int)((d->n_ctx + 31) / 32);
+    L.nublk = (L.nwords + 1023) / 1024;
+    size_t off = 0;
+    L.sim = off;    off += align_up((size_t)d->n_query * d->n_ctx * sizeof(float));
+    L.hist = off;   off += align_up((size_t)d->n_query * 3 * 2048 * sizeof(int));
+    L.prefix = off; off += align_up((size_t)d->n_query * sizeof(uint32_t));
+    L.krem = off;   off += align_up((size_t)d->n_query * sizeof(int));
+    L.blk = off;    off += align_up((size_t)d->n_query * L.nblk * 2 * sizeof(int));
+    L.bitmap = off; off += align_up((size_t)L.nwords * sizeof(uint32_t));
+    L.words = off;  off += align_up((size_t)L.nublk * sizeof(int));
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *reform_status_string(reform_status s)
+{
+    switch (s) {
+    case REFORM_OK: return "ok";
+    case REFORM_ERR_INVALID_ARG: return "invalid argument";
+    case REFORM_ERR_UNSUPPORTED: return "unsupported shape or type";
+    case REFORM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case REFORM_ERR_RUNTIME: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int32_t reform_version(void) { return 100; }
+
+// ---------------------------------------------------------------------------------------
+size_t reform_chunk_attend_score_workspace(const reform_attn_desc *d)
+{
+    if (check_attn(d) != REFORM_OK) return 0;
+    return align_up((size_t)d->n_q_heads * d->chunk_len * sizeof(float));
+}
+
+reform_status reform_chunk_attend_score(const reform_attn_desc *d, const void *q, const void *k,
+                                        const void *v, void *out, float *lse, float *score,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    reform_status rc = check_attn(d);
+    if (rc != REFORM_OK) return rc;
+    if (!q || !k || !v || !out) return REFORM_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return REFORM_ERR_INVALID_ARG;
+    float *lse_buf = lse;
+    if (!lse_buf) {
+        const size_t need = reform_chunk_attend_score_workspace(d);
+        if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & (kAlign - 1)))
+            return REFORM_ERR_WORKSPACE;
+        lse_buf = (float *)workspace;
+    }
+    AttnParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse_buf; p.score = score;
+    p.Hq = d->n_q_heads; p.Hkv = d->n_kv_heads; p.G = p.Hq / p.Hkv; p.D = d->head_dim;
+    p.M = d->cache_len; p.Ct = d->chunk_len; p.cap = d->capacity; p.n = p.M + p.Ct;
+    p.q_hs = d->q_head_stride; p.q_rs = d->q_row_stride;
+    p.o_hs = d->o_head_stride; p.o_rs = d->o_row_stride;
+    p.scale = d->scale;
+    p.W = d->obs_window ? d->obs_window : d->chunk_len;
+    p.accumulate = d->accumulate;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e;
+    if (d->dtype == REFORM_BF16) {
+        e = attend_bf16_forward(p, st);
+        if (e == hipSuccess && score) e = attend_bf16_score(p, st);
+    } else {
+        e = attend_f32_forward(p, st);
+        if (e == hipSuccess && score) e = attend_f32_score(p, st);
+    }
+    return e == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+size_t reform_evict_topk_compact_workspace(const reform_evict_desc *d)
+{
+    if (check_evict(d) != REFORM_OK) return 0;
+    const size_t rows = (size_t)d->n_kv_heads * d->budget;
+    return align_up(rows * sizeof(int32_t)) + 2 * align_up(rows * d->head_dim * elt_size(d->dtype));
+}
+
+reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, void *v, float *score,
+                                        int32_t *pos, int32_t *kept_idx, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream)
+{
+    reform_status rc = check_evict(d);
+    if (rc != REFORM_OK) return rc;
+    if (!k || !v || !score) return REFORM_ERR_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v)) return REFORM_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (d->n_valid <= d->budget) {   // nothing to evict: new_len = n_valid, no data moves
+        if (kept_idx && evict_fill_identity(kept_idx, d->n_kv_heads, d->budget, d->n_valid, st) != hipSuccess)
+            return REFORM_ERR_RUNTIME;
+        return REFORM_OK;
+    }
+    const size_t need = reform_evict_topk_compact_workspace(d);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & (kAlign - 1)))
+        return REFORM_ERR_WORKSPACE;
+    const size_t rows = (size_t)d->n_kv_heads * d->budget;
+    char *ws = (char *)workspace;
+    EvictParams p;
+    p.k = k; p.v = v; p.score = score; p.pos = pos;
+    p.kept = kept_idx ? kept_idx : (int32_t *)ws;
+    p.stage_k = ws + align_up(rows * sizeof(int32_t));
+    p.stage_v = (char *)p.stage_k + align_up(rows * d->head_dim * elt_size(d->dtype));
+    p.Hkv = d->n_kv_heads; p.n = d->n_valid; p.B = d->budget; p.cap = d->capacity;
+    p.n_sink = d->n_sink; p.n_recent = d->n_recent;
+    p.row_bytes = (int)(d->head_dim * elt_size(d->dtype));
+    return evict_run(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+size_t reform_gather_topk_workspace(const reform_gather_desc *d)
+{
+    if (check_gather(d) != REFORM_OK) return 0;
+    return gather_layout(d).total;
+}
+
+static void fill_gather(GatherParams &p, const reform_gather_desc *d, const void *emb, const void *qry)
+{
+    std::memset(&p, 0, sizeof(p));
+    p.emb = emb; p.qry = qry;
+    p.N = d->n_ctx; p.D = d->dim; p.nq = d->n_query; p.k = d->k;
+    p.radius = d->radius; p.n_head = d->n_head_keep; p.n_tail = d->n_tail_keep;
+    p.eps = d->eps;
+}
+
+reform_status reform_gather_similarity(const reform_gather_desc *d, const void *emb, const void *qry,
+                                       float *sim, void *hip_stream)
+{
+    reform_status rc = check_gather(d);
+    if (rc != REFORM_OK) return rc;
+    if (!emb || !qry || !sim || !aligned16(emb) || !aligned16(qry)) return REFORM_ERR_INVALID_ARG;
+    GatherParams p;
+    fill_gather(p, d, emb, qry);
+    p.sim = sim;
+    return gather_similarity(p, d->dtype == REFORM_BF16, (hipStream_t)hip_stream) == hipSuccess
+               ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+reform_status reform_gather_topk(const reform_gather_desc *d, const void *emb, const void *qry,
+                                 int32_t *topk_idx, float *topk_score, int32_t *union_idx,
+                                 int32_t *union_count, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream)
+{
+    reform_status rc = check_gather(d);
+    if (rc != REFORM_OK) return rc;
+    if (!emb || !qry || !topk_idx || !aligned16(emb) || !aligned16(qry)) return REFORM_ERR_INVALID_ARG;
+    if ((union_idx != nullptr) != (union_count != nullptr)) return REFORM_ERR_INVALID_ARG;
+    const GatherLayout L = gather_layout(d);
+    if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & (kAlign - 1)))
+        return REFORM_ERR_WORKSPACE;
+    char *ws = (char *)workspace;
+    GatherParams p;
+    fill_gather(p, d, emb, qry);
+    p.sim = (float *)(ws + L.sim);
+    p.topk_idx = topk_idx; p.topk_score = topk_score;
+    p.union_idx = union_idx; p.union_count = union_count;
+    p.hist = (int *)(ws + L.hist);
+    p.sel_prefix = (uint32_t *)(ws + L.prefix);
+    p.sel_krem = (int *)(ws + L.krem);
+    p.blk_cnt = (int *)(ws + L.blk);
+    p.bitmap = (uint32_t *)(ws + L.bitmap);
+    p.word_cnt = (int *)(ws + L.words);
+    p.nblk = L.nblk; p.nwords = L.nwords;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (gather_similarity(p, d->dtype == REFORM_BF16, st) != hipSuccess) return REFORM_ERR_RUNTIME;
+    return gather_select_union(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+"""The C-ABI library: loads without a GPU, exports what include/reform.h declares, and rejects
+bad descriptors on the host before anything could be launched (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_01215_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "reform.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(reform_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    names = declared_functions()
+    assert sorted(names) == sorted(binding.EXPORTED)
+    for name in names:
+        assert getattr(lib, name) is not None
+    assert lib.reform_version() >= 100
+    assert lib.reform_status_string(0) == b"ok"
+
+
+def good_attn():
+    return binding.AttnDesc(ctypes.sizeof(binding.AttnDesc), binding.REFORM_BF16, 32, 8, 128,
+                            4096, 512, 8192, 512 * 128, 128, 512 * 128, 128, 0.0884, 0, 0)
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("struct_size", 4, 1), ("dtype", 7, 1), ("n_kv_heads", 5, 1), ("chunk_len", 0, 1),
+    ("capacity", 100, 1), ("scale", 0.0, 1), ("scale", float("nan"), 1), ("obs_window", 513, 1),
+    ("accumulate", 2, 1), ("q_row_stride", 64, 1), ("q_row_stride", 129, 1), ("head_dim", 96, 2),
+])
+def test_attend_rejects_bad_descriptor(field, value, status):
+    lib = binding.load_library()
+    d = good_attn()
+    if field == "head_dim":
+        d.q_row_stride = d.o_row_stride = 96
+    setattr(d, field, value)
+    assert lib.reform_chunk_attend_score_workspace(ctypes.byref(d)) == 0
+    fake = ctypes.c_void_p(0x1000)
+    rc = lib.reform_chunk_attend_score(ctypes.byref(d), fake, fake, fake, fake, None, None, None, 0, None)
+    assert rc == status
+
+
+def test_attend_rejects_null_and_missing_workspace():
+    lib = binding.load_library()
+    d = good_attn()
+    assert lib.reform_chunk_attend_score_workspace(ctypes.byref(d)) >= 32 * 512 * 4
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.reform_chunk_attend_score(ctypes.byref(d), None, fake, fake, fake, None, None, None, 0, None) == 1
+    assert lib.reform_chunk_attend_score(ctypes.byref(d), ctypes.c_void_p(0x1004), fake, fake, fake,
+                                         None, None, None, 0, None) == 1
+    # lse == NULL needs a workspace
+    assert lib.reform_chunk_attend_score(ctypes.byref(d), fake, fake, fake, fake, None, None, None, 0, None) == 3
+    assert lib.reform_chunk_attend_score(None, fake, fake, fake, fake, None, None, None, 0, None) == 1
+
+
+def test_evict_rejects_bad_arguments():
+    lib = binding.load_library()
+    mk = lambda **kw: binding.EvictDesc(**{**dict(struct_size=ctypes.sizeof(binding.EvictDesc),
+                                                  dtype=1, n_kv_heads=8, head_dim=128, n_valid=300,
+                                                  budget=100, capacity=400, n_sink=0, n_recent=0), **kw})
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda d, ws=None, n=0: lib.reform_evict_topk_compact(ctypes.byref(d), fake, fake, fake,
+                                                                 None, None, ws, n, None)
+    assert call(mk(n_valid=500)) == 1
+    assert call(mk(n_sink=60, n_recent=60)) == 1
+    assert call(mk(budget=0)) == 1
+    assert call(mk(struct_size=8)) == 1
+    assert call(mk(head_dim=4)) == 2                      # 8-byte rows
+    assert call(mk()) == 3                                # eviction needed but no workspace
+    need = lib.reform_evict_topk_compact_workspace(ctypes.byref(mk()))
+    assert need >= 8 * 100 * 4 + 2 * 8 * 100 * 256
+    assert call(mk(), ctypes.c_void_p(0x1100), need - 1) == 3
+    assert call(mk(), ctypes.c_void_p(0x1010), need) == 3  # misaligned
+
+
+def test_gather_rejects_bad_arguments():
+    lib = binding.load_library()
+    mk = lambda **kw: binding.GatherDesc(**{**dict(struct_size=ctypes.sizeof(binding.GatherDesc),
+                                                   dtype=1, n_ctx=4096, dim=256, n_query=2, k=16,
+                                                   radius=0, n_head_keep=0, n_tail_keep=0, eps=1e-8),
+                                            **kw})
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda d, u=None, c=None: lib.reform_gather_topk(ctypes.byref(d), fake, fake, fake, None,
+                                                            u, c, None, 0, None)
+    assert call(mk(k=0)) == 1
+    assert call(mk(k=5000)) == 1
+    assert call(mk(eps=0.0)) == 1
+    assert call(mk(radius=-1)) == 1
+    assert call(mk(dim=100)) == 2
+    assert call(mk(n_ctx=1 << 31, k=16)) == 2
+    assert call(mk(), fake, None) == 1                    # union_idx without union_count
+    assert call(mk()) == 3                                # no workspace
+    assert lib.reform_gather_topk_workspace(ctypes.byref(mk())) >= 2 * 4096 * 4
+    assert lib.reform_gather_similarity(ctypes.byref(mk()), fake, fake, None, None) == 1
