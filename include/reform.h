@@ -90,6 +90,11 @@ typedef struct {
     float    scale;                          /* > 0, finite; 1/sqrt(head_dim) in the paper's models */
     int32_t  obs_window;                     /* W in [1, chunk_len]; 0 means chunk_len         */
     int32_t  accumulate;                     /* 0: score = ..., 1: score += ...                */
+    int32_t  phases;                         /* 0 or 3: attention then score (the normal call);
+                                                1: attention only (out, lse);
+                                                2: score only, reading lse written by an earlier
+                                                   phase-1 call with the same inputs (lets a
+                                                   profiler bracket each kernel separately)       */
 } reform_attn_desc;
 
 size_t reform_chunk_attend_score_workspace(const reform_attn_desc *desc);

@@ -29,7 +29,7 @@ def _lib():
                                             P, P, P]
         lib.oracle_attend_rows.restype = c_i
         lib.oracle_attend_rows.argtypes = [P, P, P, c_i, c_i, c_i, c_i, c_i, c_i, c_d, P, P, c_i,
-                                           P, P]
+                                           P, P, P]
         lib.oracle_topk_lowest_index.restype = c_i
         lib.oracle_topk_lowest_index.argtypes = [P, c_l, c_l, P]
         lib.oracle_evict_select.restype = c_i
@@ -80,8 +80,11 @@ def attend_score(q, k, v, M, scale, W=0, accumulate=False, score_in=None, want_o
     return out, lse, score
 
 
-def attend_rows(q, k, v, M, scale, rows_h, rows_i):
-    """Attention output and lse for sampled (head, row) pairs only."""
+def attend_rows(q, k, v, M, scale, rows_h, rows_i, want_score=False):
+    """Attention output and lse for sampled (head, row) pairs only.
+
+    With want_score, also the attention mass [Hkv,cap] that the SAMPLED rows alone give each key.
+    """
     q, k, v = _f32(q), _f32(k), _f32(v)
     Hq, Ct, d = q.shape
     Hkv, cap, _ = k.shape
@@ -90,10 +93,14 @@ def attend_rows(q, k, v, M, scale, rows_h, rows_i):
     n = rh.shape[0]
     out = np.zeros((n, d), np.float64)
     lse = np.zeros((n,), np.float64)
+    score = np.zeros((Hkv, cap), np.float64) if want_score else None
     rc = _lib().oracle_attend_rows(_ptr(q), _ptr(k), _ptr(v), Hq, Hkv, d, int(M), Ct, cap,
-                                   float(scale), _ptr(rh), _ptr(ri), n, _ptr(out), _ptr(lse))
+                                   float(scale), _ptr(rh), _ptr(ri), n, _ptr(out), _ptr(lse),
+                                   _ptr(score))
     if rc != 0:
         raise ValueError(f"oracle_attend_rows rc={rc}")
+    if want_score:
+        return out, lse, score
     return out, lse
 
 

@@ -143,30 +143,41 @@ int oracle_attend_score(const float *q, const float *k, const float *v,
 /* Same definition for a caller-chosen list of rows only (used to check
  * sampled outputs at sizes where the full pass would take hours).
  * rows_h[r], rows_i[r] name query head and chunk row of sample r.
- * out [nrows][d], lse [nrows].                                              */
+ * out [nrows][d], lse [nrows].  If score != NULL ([Hkv][cap], zeroed here),
+ * it receives the attention mass of the SAMPLED rows only:
+ *     score[g][j] = sum over samples r with rows_h[r]/G == g of p_{r,j}.    */
 int oracle_attend_rows(const float *q, const float *k, const float *v,
                        int Hq, int Hkv, int d, int M, int Ct, int cap,
                        double scale, const int32_t *rows_h, const int32_t *rows_i,
-                       int nrows, double *out, double *lse)
+                       int nrows, double *out, double *lse, double *score)
 {
     if (Hq <= 0 || Hkv <= 0 || Hq % Hkv || d <= 0 || M < 0 || Ct <= 0 || cap < M + Ct)
         return -1;
     const int G = Hq / Hkv;
+    const int n = M + Ct;
     int bad = 0;
+    for (int r = 0; r < nrows; ++r)
+        if (rows_h[r] < 0 || rows_h[r] >= Hq || rows_i[r] < 0 || rows_i[r] >= Ct) return -1;
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int r = 0; r < nrows; ++r) {
-        const int h = rows_h[r], i = rows_i[r];
-        if (h < 0 || h >= Hq || i < 0 || i >= Ct) { bad = 1; continue; }
-        const int g = h / G;
-        const int nvis = M + i + 1;
-        double *p = (double *)malloc(sizeof(double) * (size_t)nvis);
+    for (int g = 0; g < Hkv; ++g) {
+        double *p = (double *)malloc(sizeof(double) * (size_t)n);
         if (!p) { bad = 1; continue; }
-        attention_row(q + ((size_t)h * Ct + i) * d, k + (size_t)g * cap * d,
-                      v + (size_t)g * cap * d, d, nvis, scale, p,
-                      out + (size_t)r * d, lse + r);
+        double *sg = score ? score + (size_t)g * cap : NULL;
+        if (sg)
+            for (int j = 0; j < n; ++j) sg[j] = 0.0;
+        for (int r = 0; r < nrows; ++r) {
+            const int h = rows_h[r], i = rows_i[r];
+            if (h / G != g) continue;
+            const int nvis = M + i + 1;
+            attention_row(q + ((size_t)h * Ct + i) * d, k + (size_t)g * cap * d,
+                          v + (size_t)g * cap * d, d, nvis, scale, p,
+                          out + (size_t)r * d, lse + r);
+            if (sg)
+                for (int j = 0; j < nvis; ++j) sg[j] += p[j];
+        }
         free(p);
     }
-    return bad ? -1 : 0;
+    return bad ? -2 : 0;
 }
 
 /* ------------------------------------------------------------------------ */

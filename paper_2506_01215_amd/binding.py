@@ -40,7 +40,7 @@ class AttnDesc(ctypes.Structure):
                 ("q_head_stride", ctypes.c_int64), ("q_row_stride", ctypes.c_int64),
                 ("o_head_stride", ctypes.c_int64), ("o_row_stride", ctypes.c_int64),
                 ("scale", ctypes.c_float), ("obs_window", ctypes.c_int32),
-                ("accumulate", ctypes.c_int32)]
+                ("accumulate", ctypes.c_int32), ("phases", ctypes.c_int32)]
 
 
 class EvictDesc(ctypes.Structure):
@@ -128,18 +128,18 @@ def _check(rc, where):
 
 
 # ------------------------------------------------------------------------------------------
-def attn_desc(q, k, out, cache_len, scale, obs_window=0, accumulate=False):
+def attn_desc(q, k, out, cache_len, scale, obs_window=0, accumulate=False, phases=0):
     Hq, Ct, d = q.shape
     Hkv, cap, d2 = k.shape
     assert d2 == d and q.stride(2) == 1 and out.stride(2) == 1
     return AttnDesc(ctypes.sizeof(AttnDesc), _dtype_code(q), Hq, Hkv, d, int(cache_len), Ct, cap,
                     q.stride(0), q.stride(1), out.stride(0), out.stride(1),
-                    float(scale), int(obs_window), int(bool(accumulate)))
+                    float(scale), int(obs_window), int(bool(accumulate)), int(phases))
 
 
 def reform_chunk_attend_score(q, k, v, cache_len, scale, obs_window=0, accumulate=False,
                               out=None, lse=None, score=None, want_score=True,
-                              workspace=None, stream=None):
+                              workspace=None, stream=None, phases=0):
     """q [Hq,Ct,d]; k,v [Hkv,cap,d] (rows [0,M) cache, [M,M+Ct) chunk).  Returns (out, lse, score)."""
     lib = load_library()
     assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
@@ -151,7 +151,7 @@ def reform_chunk_attend_score(q, k, v, cache_len, scale, obs_window=0, accumulat
         if accumulate:
             raise ValueError("accumulate needs the previous score tensor")
         score = torch.zeros(k.shape[:2], dtype=torch.float32, device=q.device)
-    desc = attn_desc(q, k, out, cache_len, scale, obs_window, accumulate)
+    desc = attn_desc(q, k, out, cache_len, scale, obs_window, accumulate, phases)
     need = lib.reform_chunk_attend_score_workspace(ctypes.byref(desc))
     ws = _workspace(need, q.device, workspace)
     rc = lib.reform_chunk_attend_score(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out),

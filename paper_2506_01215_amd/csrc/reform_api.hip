@@ -38,6 +38,7 @@ reform_status check_attn(const reform_attn_desc *d)
     if (!(d->scale > 0.f) || !std::isfinite(d->scale)) return REFORM_ERR_INVALID_ARG;
     if (d->obs_window < 0 || d->obs_window > d->chunk_len) return REFORM_ERR_INVALID_ARG;
     if (d->accumulate != 0 && d->accumulate != 1) return REFORM_ERR_INVALID_ARG;
+    if (d->phases < 0 || d->phases > 3) return REFORM_ERR_INVALID_ARG;
     if (d->q_row_stride < d->head_dim || d->o_row_stride < d->head_dim) return REFORM_ERR_INVALID_ARG;
     if (d->q_head_stride < 0 || d->o_head_stride < 0) return REFORM_ERR_INVALID_ARG;
     const int per16 = (int)(16 / elt_size(d->dtype));
@@ -140,8 +141,10 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *d, const void *q
 {
     reform_status rc = check_attn(d);
     if (rc != REFORM_OK) return rc;
-    if (!q || !k || !v || !out) return REFORM_ERR_INVALID_ARG;
+    const bool do_attn = d->phases != 2, do_score = d->phases != 1 && score != nullptr;
+    if (!q || !k || !v || (do_attn && !out)) return REFORM_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return REFORM_ERR_INVALID_ARG;
+    if (d->phases == 2 && (!lse || !score)) return REFORM_ERR_INVALID_ARG;
     float *lse_buf = lse;
     if (!lse_buf) {
         const size_t need = reform_chunk_attend_score_workspace(d);
@@ -160,13 +163,13 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *d, const void *q
     p.W = d->obs_window ? d->obs_window : d->chunk_len;
     p.accumulate = d->accumulate;
     hipStream_t st = (hipStream_t)hip_stream;
-    hipError_t e;
+    hipError_t e = hipSuccess;
     if (d->dtype == REFORM_BF16) {
-        e = attend_bf16_forward(p, st);
-        if (e == hipSuccess && score) e = attend_bf16_score(p, st);
+        if (do_attn) e = attend_bf16_forward(p, st);
+        if (e == hipSuccess && do_score) e = attend_bf16_score(p, st);
     } else {
-        e = attend_f32_forward(p, st);
-        if (e == hipSuccess && score) e = attend_f32_score(p, st);
+        if (do_attn) e = attend_f32_forward(p, st);
+        if (e == hipSuccess && do_score) e = attend_f32_score(p, st);
     }
     return e == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
 }

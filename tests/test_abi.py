@@ -29,13 +29,13 @@ def test_library_exports_every_declared_symbol():
 
 def good_attn():
     return binding.AttnDesc(ctypes.sizeof(binding.AttnDesc), binding.REFORM_BF16, 32, 8, 128,
-                            4096, 512, 8192, 512 * 128, 128, 512 * 128, 128, 0.0884, 0, 0)
+                            4096, 512, 8192, 512 * 128, 128, 512 * 128, 128, 0.0884, 0, 0, 0)
 
 
 @pytest.mark.parametrize("field,value,status", [
     ("struct_size", 4, 1), ("dtype", 7, 1), ("n_kv_heads", 5, 1), ("chunk_len", 0, 1),
     ("capacity", 100, 1), ("scale", 0.0, 1), ("scale", float("nan"), 1), ("obs_window", 513, 1),
-    ("accumulate", 2, 1), ("q_row_stride", 64, 1), ("q_row_stride", 129, 1), ("head_dim", 96, 2),
+    ("accumulate", 2, 1), ("phases", 4, 1), ("q_row_stride", 64, 1), ("q_row_stride", 129, 1), ("head_dim", 96, 2),
 ])
 def test_attend_rejects_bad_descriptor(field, value, status):
     lib = binding.load_library()

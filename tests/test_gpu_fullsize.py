@@ -1,0 +1,180 @@
+"""GPU parity at the full sizes of the workloads, in the launch configuration bench.py times.
+
+A full fp64 oracle pass over a 32768 x 65536 layer-step would take hours, so at these sizes the
+checks are: sampled rows (out, lse) against the oracle; the score through inputs whose answer the
+oracle can still produce exactly -- most queries zero (closed-form uniform share, Q = 0 gives
+p = 1/(M+i+1)) plus a sample of non-zero rows whose probabilities the oracle adds row by row;
+the 128-row observation window against the oracle on that window; total attention mass; and
+whole-call exact checks wherever the oracle finishes in seconds (ragged tail, both gathers).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import assert_close, assert_selection_within_band, numpy_union, to_np
+from paper_2506_01215_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def layer_step_inputs(cfg, layer=0):
+    """Cache = chunk 0's K/V (first B rows), chunk = chunk 1; on the host, in cfg.dtype."""
+    plan = synth.adversarial_plan(cfg) if cfg.kind == "adversarial" else None
+    q0, k0, v0 = synth.chunk_qkv(cfg, layer, 0, plan=plan)
+    q1, k1, v1 = synth.chunk_qkv(cfg, layer, 1, plan=plan)
+    M = min(cfg.B, k0.shape[1])
+    K = torch.cat([k0[:, :M], k1], dim=1).contiguous()
+    V = torch.cat([v0[:, :M], v1], dim=1).contiguous()
+    return q1, K, V, M
+
+
+def sample_rows(Hq, Ct, count, seed):
+    rng = np.random.default_rng(seed)
+    edge = [0, 1, 31, 32, 63, 64, 65, 127, 128, 255, 256, Ct // 2, Ct - 65, Ct - 64, Ct - 33, Ct - 32, Ct - 2, Ct - 1]
+    edge = [i for i in edge if 0 <= i < Ct]
+    hi = np.concatenate([np.repeat(np.arange(Hq), len(edge)), rng.integers(0, Hq, count)])
+    ri = np.concatenate([np.tile(edge, Hq), rng.integers(0, Ct, count)])
+    pairs = np.unique(np.stack([hi, ri], axis=1), axis=0)
+    return pairs[:, 0].astype(np.int32), pairs[:, 1].astype(np.int32)
+
+
+def check_sparse_query_step(cfg, n_random, seed):
+    """All queries zero except a sample: expected score = uniform share + the sample's own mass."""
+    Hq, Hkv = cfg.n_q_heads, cfg.n_kv_heads
+    G = Hq // Hkv
+    q, K, V, M = layer_step_inputs(cfg)
+    Ct = q.shape[1]
+    n = M + Ct
+    rh, ri = sample_rows(Hq, Ct, n_random, seed)
+    keep = torch.zeros((Hq, Ct), dtype=torch.bool)
+    keep[torch.from_numpy(rh).long(), torch.from_numpy(ri).long()] = True
+    q = torch.where(keep[:, :, None], q, torch.zeros_like(q))
+    print(f"[fullsize] {cfg.name}: M={M} Ct={Ct} sampled rows={len(rh)}", flush=True)
+    out, lse, score = binding.reform_chunk_attend_score(q.to(DEV), K.to(DEV), V.to(DEV), M, cfg.scale)
+    torch.cuda.synchronize()
+    qn, Kn, Vn = to_np(q), to_np(K), to_np(V)
+    o_ref, l_ref, s_part = oracle.attend_rows(qn, Kn, Vn, M, cfg.scale, rh, ri, want_score=True)
+    out_h, lse_h, score_h = to_np(out), to_np(lse), to_np(score)
+    assert_close(out_h[rh, ri], o_ref, 2e-2, "out (sampled rows)")
+    assert_close(lse_h[rh, ri], l_ref, 2e-2, "lse (sampled rows)")
+    # uniform share of the zero rows: row i of head h gives 1/(M+i+1) to every key j <= M+i
+    w = 1.0 / (M + np.arange(Ct) + 1.0)
+    expect = np.zeros((Hkv, n))
+    zero_rows = ~keep.numpy()
+    for g in range(Hkv):
+        wg = (zero_rows[g * G:(g + 1) * G] * w[None, :]).sum(axis=0)        # weight of chunk row i
+        tail = np.cumsum(wg[::-1])[::-1]                                   # sum_{i' >= i}
+        expect[g] = np.concatenate([np.full(M, tail[0]), tail])
+    expect += s_part[:, :n]
+    assert_close(score_h[:, :n], expect, 2e-2, "score (uniform share + sampled rows)")
+    np.testing.assert_allclose(score_h[:, :n].sum(axis=1), G * Ct, rtol=1e-3)
+    # zero rows: out is the running mean of V, lse = log(M+i+1)
+    zi = np.array([2, 100, Ct // 3, Ct - 3])
+    zi = zi[zero_rows[0, zi]]
+    csum = np.cumsum(Vn[0, :n].astype(np.float64), axis=0)
+    for i in zi:
+        assert_close(out_h[0, i], csum[M + i] / (M + i + 1), 2e-2, f"running mean row {i}")
+        assert abs(lse_h[0, i] - np.log(M + i + 1)) < 2e-2
+    return score
+
+
+def test_workload3_layer_step_sparse_queries():
+    """32/8 heads, d 128, M = C = 32768: the shape bench.py times, W = C."""
+    check_sparse_query_step(synth.STREAMS[3], 1200, 1)
+
+
+def test_workload2_layer_step_sparse_queries():
+    """Llama-3-8B-shaped layer, M = C = 8192, log-normal key norms."""
+    check_sparse_query_step(synth.STREAMS[2], 1500, 2)
+
+
+def test_workload5_steady_step_sparse_queries():
+    """8/8 heads, M = 4096, C = 16384: sinks, needles and duplicate keys."""
+    check_sparse_query_step(synth.STREAMS[5], 1500, 3)
+
+
+def test_workload3_layer_step_dense_queries_window_and_mass():
+    """Dense random queries at full size: the 128-row observation window against the oracle
+    (the oracle sees the window as a 128-row chunk behind a cache of M + C - 128 rows, which is
+    the same set of probabilities), sampled rows, and the total mass for W = C."""
+    cfg = synth.STREAMS[3]
+    Hq, Hkv = cfg.n_q_heads, cfg.n_kv_heads
+    q, K, V, M = layer_step_inputs(cfg, layer=1)
+    Ct, W = q.shape[1], 128
+    n = M + Ct
+    qd, Kd, Vd = q.to(DEV), K.to(DEV), V.to(DEV)
+    print(f"[fullsize] dense W=128 and W=C at M={M} Ct={Ct}", flush=True)
+    out, lse, score_w = binding.reform_chunk_attend_score(qd, Kd, Vd, M, cfg.scale, obs_window=W)
+    _, _, score_c = binding.reform_chunk_attend_score(qd, Kd, Vd, M, cfg.scale)
+    torch.cuda.synchronize()
+    qn, Kn, Vn = to_np(q), to_np(K), to_np(V)
+    o_ref, l_ref, s_ref = oracle.attend_score(qn[:, Ct - W:], Kn, Vn, n - W, cfg.scale)
+    assert_close(to_np(score_w)[:, :n], s_ref[:, :n], 2e-2, "score, 128-row window")
+    assert_close(to_np(out)[:, Ct - W:], o_ref, 2e-2, "out, last 128 rows")
+    assert_close(to_np(lse)[:, Ct - W:], l_ref, 2e-2, "lse, last 128 rows")
+    sc = to_np(score_c)[:, :n]
+    assert np.all(sc >= 0)
+    np.testing.assert_allclose(sc.sum(axis=1), (Hq // Hkv) * Ct, rtol=1e-3)
+    rh, ri = sample_rows(Hq, Ct, 300, 4)
+    o2, l2 = oracle.attend_rows(qn, Kn, Vn, M, cfg.scale, rh, ri)
+    assert_close(to_np(out)[rh, ri], o2, 2e-2, "out (sampled rows, dense)")
+    assert_close(to_np(lse)[rh, ri], l2, 2e-2, "lse (sampled rows, dense)")
+
+
+def test_workload5_ragged_tail_exact():
+    """Last chunk of workload 5: 17 rows over a full 4096-row cache, n = 4113 -> 4096."""
+    cfg = synth.STREAMS[5]
+    plan = synth.adversarial_plan(cfg)
+    t_last = cfg.n_chunks - 1
+    assert cfg.chunk_len(t_last) == 17
+    _, kc, vc = synth.chunk_qkv(cfg, 0, t_last - 1, plan=plan)      # stands in for the retained cache
+    q, k, v = synth.chunk_qkv(cfg, 0, t_last, plan=plan)
+    M, Ct, B = cfg.B, 17, cfg.B
+    K = torch.cat([kc[:, :M], k], dim=1).contiguous()
+    V = torch.cat([vc[:, :M], v], dim=1).contiguous()
+    K[:, 100] = K[:, 7]                                             # exact duplicates in the cache
+    K[:, 4000] = K[:, 7]
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    out, lse, score = binding.reform_chunk_attend_score(q.to(DEV), Kd, Vd, M, cfg.scale)
+    o_ref, l_ref, s_ref = oracle.attend_score(to_np(q), to_np(K), to_np(V), M, cfg.scale)
+    n = M + Ct
+    assert_close(to_np(out), o_ref, 2e-2, "out")
+    assert_close(to_np(lse), l_ref, 2e-2, "lse")
+    assert_close(to_np(score)[:, :n], s_ref[:, :n], 2e-2, "score")
+    assert torch.equal(score[:, 100], score[:, 7]) and torch.equal(score[:, 4000], score[:, 7])
+    kept = torch.empty((cfg.n_kv_heads, B), dtype=torch.int32, device=DEV)
+    binding.reform_evict_topk_compact(Kd, Vd, score, n, B, kept_idx=kept)
+    torch.cuda.synchronize()
+    for g in range(cfg.n_kv_heads):
+        assert_selection_within_band(kept[g].cpu().numpy(), s_ref[g, :n], B, 2e-2, f"kept head {g}")
+
+
+def check_gather_full(gcfg):
+    emb, qry = synth.gather_inputs(gcfg, DEV)
+    print(f"[fullsize] gather {gcfg.name}", flush=True)
+    sim = binding.reform_gather_similarity(emb, qry)
+    idx, sc, uni, cnt = binding.reform_gather_topk(emb, qry, gcfg.k, gcfg.radius)
+    torch.cuda.synchronize()
+    sim_ref = oracle.cosine(to_np(emb), to_np(qry))
+    assert_close(sim.cpu().numpy(), sim_ref, 2e-2, "sim")
+    idx_h = idx.cpu().numpy()
+    subs = 0
+    for qi in range(gcfg.n_query):
+        subs += assert_selection_within_band(idx_h[qi], sim_ref[qi], gcfg.k, 2e-2, f"topk q={qi}")
+    got = uni.cpu().numpy()[:int(cnt.item())]
+    np.testing.assert_array_equal(got, numpy_union(idx_h, gcfg.N, gcfg.radius, 0, 0))
+    if subs == 0:
+        topk_ref = np.stack([oracle.topk_lowest_index(sim_ref[qi], gcfg.k) for qi in range(gcfg.n_query)])
+        np.testing.assert_array_equal(idx_h, topk_ref)
+        np.testing.assert_array_equal(got, oracle.union_dilate(topk_ref, gcfg.N, gcfg.radius))
+    print(f"[fullsize] gather {gcfg.name}: union {len(got)} rows, {subs} in-band substitutions", flush=True)
+
+
+def test_workload2_gather_full():
+    check_gather_full(synth.GATHERS[2])
+
+
+def test_workload4_gather_full():
+    check_gather_full(synth.GATHERS[4])

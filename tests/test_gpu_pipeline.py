@@ -1,0 +1,117 @@
+"""GPU parity of the whole recurrent pass: chunk attention + score -> retention -> compaction,
+chunk after chunk, against the fp64 oracle in lock-step.
+
+Lock-step: before every chunk the oracle's cache is rebuilt from the ORIGINAL seeded K/V rows of
+the tokens the GPU currently holds (identified by the integer token ids that travel with the rows).
+Only the identity of a retained token can therefore come from the GPU, and only after that
+choice was validated against the oracle's scores; no floating-point value ever does.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import RTOL, assert_close, assert_selection_within_band, to_np
+from paper_2506_01215_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0):
+    Hq, Hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    cap, B = cfg.capacity, cfg.B
+    rtol = RTOL[cfg.dtype]
+    plan = synth.adversarial_plan(cfg) if cfg.kind == "adversarial" else None
+    Kd = torch.zeros((Hkv, cap, d), dtype=cfg.dtype, device=DEV)
+    Vd = torch.zeros_like(Kd)
+    pos = torch.full((Hkv, cap), -1, dtype=torch.int32, device=DEV)
+    K_all = np.zeros((Hkv, cfg.L, d), np.float32)      # every token's original key / value
+    V_all = np.zeros((Hkv, cfg.L, d), np.float32)
+    M, subs_total, stats = 0, 0, []
+    for t in range(cfg.n_chunks):
+        q, k, v = synth.chunk_qkv(cfg, layer, t, plan=plan)
+        Ct = q.shape[1]
+        base = t * cfg.C
+        K_all[:, base:base + Ct] = to_np(k)
+        V_all[:, base:base + Ct] = to_np(v)
+        n = M + Ct
+        Kd[:, M:n] = k.to(DEV)
+        Vd[:, M:n] = v.to(DEV)
+        pos[:, M:n] = torch.arange(base, base + Ct, dtype=torch.int32, device=DEV)
+        pos_before = pos.cpu().numpy()
+        print(f"[pipeline] {cfg.name} chunk {t}/{cfg.n_chunks} M={M} Ct={Ct}", flush=True)
+        out, lse, score = binding.reform_chunk_attend_score(q.to(DEV), Kd, Vd, M, cfg.scale)
+        kept = torch.full((Hkv, B), -1, dtype=torch.int32, device=DEV)
+        score_gpu = score.cpu().numpy()
+        new_len = binding.reform_evict_topk_compact(Kd, Vd, score, n, B, n_sink, n_recent, pos=pos,
+                                                    kept_idx=kept)
+        torch.cuda.synchronize()
+        kept_h = kept.cpu().numpy()
+        pos_after = pos.cpu().numpy()
+        # structural checks on every chunk (cheap): the compaction moved the right original rows
+        Kh, Vh = to_np(Kd), to_np(Vd)
+        for g in range(Hkv):
+            kg = kept_h[g, :new_len]
+            assert np.all(np.diff(kg) > 0) and kg[0] >= 0 and kg[-1] < n
+            np.testing.assert_array_equal(pos_after[g, :new_len], pos_before[g, kg])
+            np.testing.assert_array_equal(Kh[g, :new_len], K_all[g, pos_after[g, :new_len]])
+            np.testing.assert_array_equal(Vh[g, :new_len], V_all[g, pos_after[g, :new_len]])
+            # the selection is exact on the GPU's own fp32 scores: larger first, then lower slot
+            s = score_gpu[g, :n].astype(np.float64)
+            if n > B:
+                forced = np.zeros(n, bool)
+                forced[:n_sink] = True
+                forced[n - n_recent:] = n_recent > 0
+                key = np.where(forced, np.inf, s)
+                want = np.sort(np.lexsort((np.arange(n), -key))[:B])
+                np.testing.assert_array_equal(kg, want)
+        if check_chunks is None or t in check_chunks:
+            Ko = np.zeros((Hkv, cap, d), np.float32)
+            Vo = np.zeros((Hkv, cap, d), np.float32)
+            for g in range(Hkv):
+                Ko[g, :n] = K_all[g, pos_before[g, :n]]
+                Vo[g, :n] = V_all[g, pos_before[g, :n]]
+            o_ref, l_ref, s_ref = oracle.attend_score(to_np(q), Ko, Vo, M, cfg.scale)
+            assert_close(to_np(out), o_ref, rtol, f"out chunk {t}")
+            assert_close(to_np(lse), l_ref, rtol, f"lse chunk {t}")
+            assert_close(score_gpu[:, :n], s_ref[:, :n], rtol, f"score chunk {t}")
+            for g in range(Hkv):
+                forced = list(range(min(n_sink, n))) + list(range(max(n - n_recent, 0), n)) if n > B else []
+                subs_total += assert_selection_within_band(kept_h[g, :new_len], s_ref[g, :n], new_len,
+                                                           rtol, f"kept chunk {t} head {g}", forced)
+        stats.append(pos_after[:, :new_len].copy())
+        M = new_len
+    return stats, subs_total, plan
+
+
+def test_workload1_fp32_full_pass():
+    """The tiny fp32 stream, every chunk of it (16 chunks of 128, budget 256)."""
+    stats, subs, _ = lockstep(synth.STREAMS[1])
+    assert len(stats) == 16 and stats[-1].shape == (4, 256)
+    print(f"[pipeline] workload 1: {subs} in-band substitutions over 16 chunks", flush=True)
+
+
+def test_workload2_scaled_bf16_pass():
+    cfg = synth.scaled(synth.STREAMS[2], L=6 * 640, C=640, B=640)
+    lockstep(cfg)
+
+
+def test_workload3_scaled_lowrank_pass_with_protected_tokens():
+    cfg = synth.scaled(synth.STREAMS[3], L=4 * 768 + 100, C=768, B=512, n_layers=1)
+    stats, _, _ = lockstep(cfg, n_sink=16, n_recent=32, layer=3)
+    for s in stats[1:]:
+        assert (s[:, :16] == np.arange(16)).all()          # the sinks never leave
+
+
+def test_workload5_scaled_adversarial_ragged_ties():
+    """Sinks, needles, exact duplicate keys and a 17-token last chunk."""
+    cfg = synth.scaled(synth.STREAMS[5], L=5 * 1024 + 17, C=1024, B=384)
+    stats, _, plan = lockstep(cfg)
+    assert cfg.chunk_len(cfg.n_chunks - 1) == 17
+    final = stats[-1]
+    for g in range(cfg.n_kv_heads):
+        assert set(range(4)) <= set(final[g].tolist()), "attention sinks were evicted"
+    needles = set(plan["needle_pos"].tolist())
+    survived = np.mean([len(needles & set(final[g].tolist())) for g in range(cfg.n_kv_heads)])
+    print(f"[pipeline] workload 5 (scaled): {survived:.1f} of 64 needles in the final cache", flush=True)

@@ -198,6 +198,30 @@ def test_sampled_rows_equal_full_pass():
     np.testing.assert_array_equal(l2, l[rh, ri])
 
 
+def test_sampled_row_score_is_the_mass_of_those_rows():
+    """Zero queries give a closed-form share; the sampled rows add their own probabilities."""
+    rng = np.random.default_rng(8)
+    Hq, Hkv, d, M, Ct = 4, 2, 8, 7, 11
+    q, k, v = rand_case(rng, Hq, Hkv, d, M, Ct)
+    rh = np.array([0, 1, 3, 2, 0], np.int32)
+    ri = np.array([0, 10, 4, 4, 6], np.int32)
+    keep = np.zeros((Hq, Ct), bool)
+    keep[rh, ri] = True
+    q[~keep] = 0.0
+    _, _, full = oracle.attend_score(q, k, v, M, 0.3)
+    _, _, part = oracle.attend_rows(q, k, v, M, 0.3, rh, ri, want_score=True)
+    uniform = np.zeros_like(full)
+    for h in range(Hq):
+        for i in range(Ct):
+            if not keep[h, i]:
+                uniform[h // 2, :M + i + 1] += 1.0 / (M + i + 1)
+    np.testing.assert_allclose(part + uniform, full, rtol=1e-12, atol=1e-14)
+    # sampling every row reproduces the full score
+    hh, ii = np.meshgrid(np.arange(Hq), np.arange(Ct), indexing="ij")
+    _, _, allrows = oracle.attend_rows(q, k, v, M, 0.3, hh.ravel(), ii.ravel(), want_score=True)
+    np.testing.assert_allclose(allrows, full, rtol=1e-12, atol=1e-14)
+
+
 def test_bad_arguments_rejected():
     rng = np.random.default_rng(7)
     q, k, v = rand_case(rng, 3, 2, 4, 2, 3)      # Hq % Hkv != 0
