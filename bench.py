@@ -37,7 +37,7 @@ def parse():
 
 def cpu_baseline(cfg, q_mid, K, V, M):
     """The fp64 oracle, as it stands, on a bounded sample of the same layer-step: the middle
-    128 rows of the chunk (their cost is the chunk's average), all heads, against the full
+    rows of the chunk (their cost is the chunk's average), all heads, against the full
     [cache || chunk] key set, plus the per-head selection.  Extrapolated to 32 layers."""
     import numpy as np
     import oracle
@@ -174,7 +174,7 @@ def main():
     if not args.no_cpu_baseline:
         to_np = lambda t: t.detach().float().cpu().numpy()
         q, k, v = inputs[0][0]
-        half = 64
+        half = 512
         rows = slice(C // 2 - half, C // 2 + half)
         Mo = M + C // 2 - half
         Kh = torch.cat([Kc[0][:, :M], k[:, :C // 2 + half]], dim=1)
