@@ -24,7 +24,7 @@ namespace reform {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-__device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c)
+__device__ __forceinline__ f32x16 mfma32(v4u a, v4u b, f32x16 c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
 }
@@ -39,26 +39,166 @@ __device__ __forceinline__ int vt_pos(int key)
 }
 
 // ------------------------------------------------------------------------------------------
-// Forward: out, lse.  One workgroup = NW waves; a wave owns 32*QB chunk rows of one query head.
-// The waves of a workgroup cover `gp` query heads of one KV group times NW/gp row slabs, so the
-// K/V tiles staged in LDS serve every wave.
-template <int D, int QB, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_fwd_bf16(AttnParams p)
+// Global -> register -> LDS staging of one 64-key K/V tile by a workgroup of NT threads.
+// K rows are copied as they are (row pitch D+8 elements).  V is transposed: thread (v_dq, v_k0)
+// holds an 8-wide d slice of PIECES consecutive keys and writes, for each of the 8 d rows,
+// PIECES consecutive bf16.  Inside a V^T row (64 keys = eight 16-byte chunks + pad) the chunk
+// index is XOR-ed with (row/32)%8.  Measured on gfx950: with the 144-byte pitch alone a
+// fragment read costs ~5 clk per wave but the transposing writes collide 16-way (32 clk per
+// dword); this swizzle is constant over a fragment read (so reads stay conflict-free) and cuts
+// the write cost to ~8 clk.  Finer swizzles (row/8, row/16) made the reads 2-3x slower.
+template <int D, int NT>
+struct TileStage {
+    static constexpr int BN = 64;
+    static constexpr int KROW = D + 8;
+    static constexpr int VROW = BN + 8;
+    static constexpr int C8 = D / 8;
+    static constexpr int PIECES = BN * C8 / NT;
+    static_assert(PIECES == 1 || PIECES == 2 || PIECES == 4, "tile/threads mismatch");
+    v4u kpre[PIECES], vpre[PIECES];
+    uint32_t k_goff, v_goff;      // byte offsets of this thread's first piece inside a tile (global)
+    uint32_t k_loff, v_loff;      // element offsets inside an LDS tile
+    int k_row, v_row;             // tile-relative rows of the first piece (for the clamped tail path)
+
+    __device__ __forceinline__ void init(int tid)
+    {
+        const int v_dq = tid % C8, v_k0 = (tid / C8) * PIECES;
+        k_row = tid / C8;
+        v_row = v_k0;
+        k_goff = (uint32_t)(k_row * D + (tid % C8) * 8) * 2u;
+        v_goff = (uint32_t)(v_k0 * D + v_dq * 8) * 2u;
+        k_loff = (uint32_t)(k_row * KROW + (tid % C8) * 8);
+        const int pos = vt_pos(v_k0);
+        const int sw = (v_dq >> 2) & 7;
+        v_loff = (uint32_t)(v_dq * 8 * VROW + ((((pos >> 3) ^ sw) << 3) | (pos & 7)));
+    }
+    // Kt, Vt: tile base pointers (uniform); rows_left = n - j0 (>= 1).  Piece i of K sits NT/C8 rows
+    // further down, piece i of V one row further down.
+    __device__ __forceinline__ void load(const u16 *Kt, const u16 *Vt, int rows_left)
+    {
+        const char *kb = (const char *)Kt, *vb = (const char *)Vt;
+        if (rows_left >= BN) {
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                kpre[i] = *(const v4u *)(kb + (k_goff + (uint32_t)(i * (NT / C8) * D * 2)));
+                vpre[i] = *(const v4u *)(vb + (v_goff + (uint32_t)(i * D * 2)));
+            }
+        } else {   // ragged last tile: rows past the end repeat the last valid row
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                const int kr = k_row + i * (NT / C8), vr = v_row + i;
+                const int kd = kr < rows_left ? 0 : kr - (rows_left - 1);
+                const int vd = vr < rows_left ? 0 : vr - (rows_left - 1);
+                kpre[i] = *(const v4u *)(kb + (k_goff + (uint32_t)((i * (NT / C8) - kd) * D * 2)));
+                vpre[i] = *(const v4u *)(vb + (v_goff + (uint32_t)((i - vd) * D * 2)));
+            }
+        }
+    }
+    __device__ __forceinline__ void store(u16 *dk, u16 *dv) const
+    {
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) *(v4u *)(dk + k_loff + i * (NT / C8) * KROW) = kpre[i];
+        u16 *dst0 = dv + v_loff;
+#pragma unroll
+        for (int dd = 0; dd < 8; ++dd) {
+            u16 e[PIECES];
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                const uint32_t w = (dd >> 1) == 0 ? vpre[i].x : (dd >> 1) == 1 ? vpre[i].y
+                                   : (dd >> 1) == 2 ? vpre[i].z : vpre[i].w;
+                e[i] = (dd & 1) ? (u16)(w >> 16) : (u16)(w & 0xffffu);
+            }
+            u16 *dst = dst0 + dd * VROW;
+            if constexpr (PIECES == 4) {
+                v2u w2;
+                w2.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
+                w2.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
+                *(v2u *)dst = w2;
+            } else if constexpr (PIECES == 2) {
+                *(uint32_t *)dst = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
+            } else {
+                *dst = e[0];
+            }
+        }
+    }
+};
+
+__device__ __forceinline__ float dot2_ones(uint32_t packed, float acc)
 {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed),
+                                           __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
+
+// p = exp2(s*c - mc) for the 32 logits a lane holds of one 64-key tile, packed to bf16 as the four
+// B operands of P.V; returns the lane's partial row sum of the ROUNDED probabilities.
+__device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, float mc, v4u (&pb)[4])
+{
+    float rs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        float pv[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -mc));
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            v4u w;
+            w.x = pack_bf16x2(pv[8 * hh + 0], pv[8 * hh + 1]);
+            w.y = pack_bf16x2(pv[8 * hh + 2], pv[8 * hh + 3]);
+            w.z = pack_bf16x2(pv[8 * hh + 4], pv[8 * hh + 5]);
+            w.w = pack_bf16x2(pv[8 * hh + 6], pv[8 * hh + 7]);
+            rs = dot2_ones(w.x, rs);
+            rs = dot2_ones(w.y, rs);
+            rs = dot2_ones(w.z, rs);
+            rs = dot2_ones(w.w, rs);
+            pb[kb * 2 + hh] = w;
+        }
+    }
+    return rs;
+}
+
+// Forward: out, lse.  One workgroup = 8 waves; a wave owns 32 chunk rows of one query head.  The
+// waves of a workgroup cover `gp` query heads of one KV group times 8/gp row slabs, so the K/V
+// tiles staged in LDS (double-buffered, one barrier per 64-key tile) serve every wave.
+//
+// Measured on gfx950: while a v_mfma_f32_32x32x16_bf16 of one wave occupies a SIMD's matrix pipe,
+// ordinary VALU instructions of the other wave on that SIMD do not issue (a wave doing only
+// MFMAs next to a wave doing only v_fma takes the SUM of their solo times; only transcendental
+// ops overlap).  The cost of a tile is therefore MFMA time + VALU time, and this kernel is built
+// to keep the VALU instruction count per tile small:
+//   - no row maximum on the fast path: probabilities are formed against the current reference
+//     m_run; if a row outgrew it by more than kBigSum (or m_run is still -inf) the tile sum of
+//     that row is huge / inf / NaN, and only then the whole wave recomputes with the true maximum
+//     and rescales its 16*DB accumulators once;
+//   - the row sum comes from the bf16-rounded probabilities with v_dot2 (two per instruction),
+//     i.e. from exactly the weights that multiply V;
+//   - scale*log2(e) folded into one v_fma per logit, v_exp_f32 directly, packed bf16 converts;
+//   - tile addresses are a uniform base plus per-thread constants computed once.
+constexpr float kBigSum = 65536.0f;
+constexpr int kFwdWaves = 8;
+
+template <int D>
+constexpr size_t fwd_lds_bytes()
+{
+    return sizeof(u16) * (size_t)(2 * 64 * (D + 8) + 2 * D * (64 + 8));
+}
+
+template <int D>
+__global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
+{
+    constexpr int NW = kFwdWaves;
     constexpr int NT = NW * 64;
     constexpr int KS = D / 16;           // MFMA k-steps of Q.K^T
     constexpr int DB = D / 32;           // 32-wide output blocks of P.V
-    constexpr int BN = 64;               // keys per tile
-    constexpr int KROW = D + 8;          // LDS row pitch (elements), 16 B pad
-    constexpr int VROW = BN + 8;
-    constexpr int C8 = D / 8;            // 16-byte pieces per K/V row
-    constexpr int PIECES = BN * C8 / NT; // pieces of K (and keys of V) per thread per tile
-    static_assert(PIECES >= 1 && PIECES <= 4, "tile/threads mismatch");
-    constexpr int WROWS = 32 * QB;
+    using Stage = TileStage<D, NT>;
+    constexpr int BN = Stage::BN, KROW = Stage::KROW, VROW = Stage::VROW;
+    constexpr int KTILE = BN * KROW, VTILE = D * VROW;
+    constexpr int kWin = 8;              // fragment prefetch distance (register quads)
+    constexpr int NV = 4 * DB, NK = 2 * KS;
 
     extern __shared__ __attribute__((aligned(16))) u16 smem[];
-    u16 *ldsK = smem;                          // [2][BN*KROW]
-    u16 *ldsV = smem + 2 * BN * KROW;          // [2][D*VROW]
+    u16 *ldsK = smem;                          // [2][KTILE]
+    u16 *ldsV = smem + 2 * KTILE;              // [2][VTILE]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -75,214 +215,150 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_bf16(AttnParams p)
     const int rb = p.n_row_blocks - 1 - rest / nsub;
     const int slabs = NW / p.gp;
     const int head = kvh * p.G + hs * p.gp + (wave % p.gp);
-    const int rwg = slabs * WROWS;
-    const int w0 = rb * rwg + (wave / p.gp) * WROWS;
+    const int rwg = slabs * 32;
+    const int w0 = rb * rwg + (wave / p.gp) * 32;
 
     const u16 *Kg = (const u16 *)p.k + (size_t)kvh * p.cap * D;
     const u16 *Vg = (const u16 *)p.v + (size_t)kvh * p.cap * D;
 
     // Q^T operands stay in registers for the whole pass
-    uint4 qreg[QB][KS];
+    v4u qreg[KS];
     {
         const u16 *Qh = (const u16 *)p.q + (size_t)head * p.q_hs;
+        int row = w0 + ln;
+        row = row < p.Ct ? row : p.Ct - 1;
+        const u16 *src = Qh + (size_t)row * p.q_rs + 8 * lg;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            int row = w0 + qb * 32 + ln;
-            row = row < p.Ct ? row : p.Ct - 1;
-            const u16 *src = Qh + (size_t)row * p.q_rs + 8 * lg;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) qreg[qb][ks] = *(const uint4 *)(src + ks * 16);
-        }
+        for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const v4u *)(src + ks * 16);
     }
 
     const int wg_last_row = min(rb * rwg + rwg, p.Ct) - 1;
     const int ntiles = (p.M + wg_last_row) / BN + 1;
-    const int wave_last_key = (w0 < p.Ct) ? p.M + min(w0 + WROWS, p.Ct) - 1 : -1;
+    const int wave_last_key = (w0 < p.Ct) ? p.M + min(w0 + 32, p.Ct) - 1 : -1;
 
-    f32x16 o[QB][DB];
-    float m_run[QB], l_run[QB];
+    f32x16 o[DB];
+    float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o[qb][db][e] = 0.f;
-    }
-
-    // per-thread slice of a tile for the global -> LDS copy
-    uint4 kpre[PIECES], vpre[PIECES];
-    const int v_dq = tid % C8;            // which 8-wide d slice of V this thread transposes
-    const int v_k0 = (tid / C8) * PIECES; // first of its PIECES consecutive keys
-    auto load_tile = [&](int t) {
-        const int j0 = t * BN;
-#pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
-            const int idx = tid + NT * i;
-            int row = j0 + idx / C8;
-            row = row < p.n ? row : p.n - 1;
-            kpre[i] = *(const uint4 *)(Kg + (size_t)row * D + (idx % C8) * 8);
-            int vrow = j0 + v_k0 + i;
-            vrow = vrow < p.n ? vrow : p.n - 1;
-            vpre[i] = *(const uint4 *)(Vg + (size_t)vrow * D + v_dq * 8);
-        }
-    };
-    auto store_tile = [&](int buf) {
-        u16 *dk = ldsK + buf * BN * KROW;
-        u16 *dv = ldsV + buf * D * VROW;
-#pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
-            const int idx = tid + NT * i;
-            *(uint4 *)(dk + (idx / C8) * KROW + (idx % C8) * 8) = kpre[i];
-        }
-        const int pos = vt_pos(v_k0);
-#pragma unroll
-        for (int dd = 0; dd < 8; ++dd) {
-            // element dd of each of this thread's keys -> PIECES consecutive bf16 of row v_dq*8+dd
-            u16 e[PIECES];
-#pragma unroll
-            for (int i = 0; i < PIECES; ++i) {
-                const uint32_t w = (dd >> 1) == 0 ? vpre[i].x : (dd >> 1) == 1 ? vpre[i].y
-                                   : (dd >> 1) == 2 ? vpre[i].z : vpre[i].w;
-                e[i] = (dd & 1) ? (u16)(w >> 16) : (u16)(w & 0xffffu);
-            }
-            u16 *dst = dv + (v_dq * 8 + dd) * VROW + pos;
-            if constexpr (PIECES == 4) {
-                uint2 w2;
-                w2.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
-                w2.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
-                *(uint2 *)dst = w2;
-            } else if constexpr (PIECES == 2) {
-                *(uint32_t *)dst = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
-            } else {
-                *dst = e[0];
-            }
-        }
-    };
+        for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
 
     const float c = p.scale * kLog2e;
+    // per-lane fragment offsets (elements) inside a K tile / V^T tile
+    const int k_frag0 = ln * KROW + 8 * lg;
+    const int v_frag0 = ln * VROW;
 
-    load_tile(0);
-    store_tile(0);
-    if (ntiles > 1) load_tile(1);
+    Stage st;
+    st.init(tid);
+    st.load(Kg, Vg, p.n);
+    st.store(ldsK, ldsV);
+    if (ntiles > 1) st.load(Kg + BN * D, Vg + BN * D, p.n - BN);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
         const int j0 = t * BN;
         if (j0 <= wave_last_key) {
-            const u16 *sk = ldsK + buf * BN * KROW;
-            const u16 *sv = ldsV + buf * D * VROW;
-            // ---- S^T = K Q^T for 64 keys x (32*QB) queries
-            f32x16 s[2][QB];
+            const u16 *sk = ldsK + buf * KTILE + k_frag0;
+            const u16 *sv = ldsV + buf * VTILE + v_frag0;
+            auto kfrag = [&](int i) -> v4u {     // i = 2*ks + kb
+                return *(const v4u *)(sk + (i & 1) * 32 * KROW + (i >> 1) * 16);
+            };
+            auto vfrag = [&](int i) -> v4u {     // i = DB*t16 + db; XOR swizzle (row/32)%8 = db
+                const int t16 = i / DB, db = i % DB;
+                return *(const v4u *)(sv + db * 32 * VROW + ((2 * t16 + lg) ^ (db & 7)) * 8);
+            };
+            // ---- S^T = K Q^T; fragments stream through a rolling window of kWin register quads;
+            // the window is refilled with the first V^T fragments while the last MFMAs run
+            v4u fw[kWin];
+#pragma unroll
+            for (int i = 0; i < kWin; ++i) fw[i] = kfrag(i);
+            f32x16 s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
+                for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) s[kb][qb][e] = 0.f;
+            for (int f = 0; f < NK; ++f) {
+                s[f & 1] = mfma32(fw[f % kWin], qreg[f >> 1], s[f & 1]);
+                const int g = f + kWin;
+                fw[f % kWin] = g < NK ? kfrag(g) : vfrag(g - NK);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, kWin, 0);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const uint4 a = *(const uint4 *)(sk + (kb * 32 + ln) * KROW + ks * 16 + 8 * lg);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) s[kb][qb] = mfma32(a, qreg[qb][ks], s[kb][qb]);
-                }
+            for (int f = 0; f < NK; ++f) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
             // ---- causal mask on tiles that reach past the first row of this wave
             if (j0 + BN - 1 > p.M + w0) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    const int lim = p.M + w0 + qb * 32 + ln - j0;   // key offset <= lim is visible
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) {
-                            const int koff = kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
-                            if (koff > lim) s[kb][qb][e] = -INFINITY;
-                        }
-                }
-            }
-            // ---- online softmax; probabilities packed to bf16 as B operands of P.V
-            uint4 pb[QB][4];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float mx = m_run[qb];
+                asm volatile("; mask path" ::: "memory");      // diagonal tiles only: keep out of line
+                const int lim = p.M + w0 + ln - j0;   // key offset <= lim is visible
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][qb][e]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - mx) * c);
-                m_run[qb] = mx;
-                const float mc = mx * c;
-                float rs = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    float pv[16];
-#pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][qb][e], c, -mc));
-                        rs += pv[e];
+                        const int koff = kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
+                        if (koff > lim) s[kb][e] = -INFINITY;
                     }
+            }
+            // ---- softmax (see the header comment)
+            v4u pb[4];
+            float rs = softmax_tile(s, c, m_run * c, pb);
+            if (__builtin_amdgcn_ballot_w64(!(rs < kBigSum)) != 0ull) {
+                asm volatile("; rescale path" ::: "memory");   // keeps this rare block out of line
+                float mx = s[0][0];
 #pragma unroll
-                    for (int hh = 0; hh < 2; ++hh) {
-                        uint4 w;
-                        w.x = pack_bf16x2(pv[8 * hh + 0], pv[8 * hh + 1]);
-                        w.y = pack_bf16x2(pv[8 * hh + 2], pv[8 * hh + 3]);
-                        w.z = pack_bf16x2(pv[8 * hh + 4], pv[8 * hh + 5]);
-                        w.w = pack_bf16x2(pv[8 * hh + 6], pv[8 * hh + 7]);
-                        pb[qb][kb * 2 + hh] = w;
-                    }
-                }
-                l_run[qb] = l_run[qb] * alpha + rs;
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(mx, m_run);
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+                m_run = m_new;
+                l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) o[qb][db][e] *= alpha;
+                    for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+                rs = softmax_tile(s, c, m_run * c, pb);
             }
-            // ---- O^T += V^T P^T
+            l_run += rs;
+            // ---- O^T += V^T P^T (DB independent chains), rest of the V^T fragments
 #pragma unroll
-            for (int t16 = 0; t16 < 4; ++t16) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const uint4 a = *(const uint4 *)(sv + (db * 32 + ln) * VROW + t16 * 16 + 8 * lg);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) o[qb][db] = mfma32(a, pb[qb][t16], o[qb][db]);
-                }
+            for (int f = 0; f < NV; ++f) {
+                o[f % DB] = mfma32(fw[f % kWin], pb[f / DB], o[f % DB]);
+                if (f + kWin < NV) fw[f % kWin] = vfrag(f + kWin);
             }
         }
         // stage tile t+1 (already in registers) into the other buffer, prefetch tile t+2
         if (t + 1 < ntiles) {
-            store_tile(buf ^ 1);
-            if (t + 2 < ntiles) load_tile(t + 2);
+            st.store(ldsK + (buf ^ 1) * KTILE, ldsV + (buf ^ 1) * VTILE);
+            if (t + 2 < ntiles) {
+                const size_t off = (size_t)(j0 + 2 * BN) * D;
+                st.load(Kg + off, Vg + off, p.n - (j0 + 2 * BN));
+            }
         }
         __syncthreads();
     }
 
     if (wave_last_key < 0) return;
     u16 *Oh = (u16 *)p.out + (size_t)head * p.o_hs;
+    const int row = w0 + ln;
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (row >= p.Ct) return;
+    const float inv = 1.0f / l_tot;
+    u16 *dst = Oh + (size_t)row * p.o_rs;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int row = w0 + qb * 32 + ln;
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-        if (row >= p.Ct) continue;
-        const float inv = 1.0f / l_tot;
-        u16 *dst = Oh + (size_t)row * p.o_rs;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                uint2 w;
-                w.x = pack_bf16x2(o[qb][db][4 * b + 0] * inv, o[qb][db][4 * b + 1] * inv);
-                w.y = pack_bf16x2(o[qb][db][4 * b + 2] * inv, o[qb][db][4 * b + 3] * inv);
-                *(uint2 *)(dst + db * 32 + 8 * b + 4 * lg) = w;
-            }
-        if (lg == 0)
-            p.lse[(size_t)head * p.Ct + row] = (m_run[qb] * c + __builtin_amdgcn_logf(l_tot)) * kLn2;
-    }
+        for (int b = 0; b < 4; ++b) {
+            v2u w;
+            w.x = pack_bf16x2(o[db][4 * b + 0] * inv, o[db][4 * b + 1] * inv);
+            w.y = pack_bf16x2(o[db][4 * b + 2] * inv, o[db][4 * b + 3] * inv);
+            *(v2u *)(dst + db * 32 + 8 * b + 4 * lg) = w;
+        }
+    if (lg == 0) p.lse[(size_t)head * p.Ct + row] = (m_run * c + __builtin_amdgcn_logf(l_tot)) * kLn2;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -318,14 +394,14 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
     const int jw = j_wg + wave * WKEYS;
 
     const u16 *Kg = (const u16 *)p.k + (size_t)kvh * p.cap * D;
-    uint4 kreg[KB][KS];
+    v4u kreg[KB][KS];
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
         int key = jw + kb * 32 + ln;
         key = key < p.n ? key : p.n - 1;
         const u16 *src = Kg + (size_t)key * D + 8 * lg;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kreg[kb][ks] = *(const uint4 *)(src + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) kreg[kb][ks] = *(const v4u *)(src + ks * 16);
     }
 
     f32x16 col[KB];
@@ -341,7 +417,7 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
     const int iters = p.G * ntq;
     const float c = p.scale * kLog2e;
 
-    uint4 qpre[PIECES];
+    v4u qpre[PIECES];
     float lpre = 0.f;
     auto load_q = [&](int it) {
         const int hh = it / ntq;
@@ -353,7 +429,7 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
             const int idx = tid + NT * i;
             int row = i0 + idx / C8;
             row = row < p.Ct ? row : p.Ct - 1;
-            qpre[i] = *(const uint4 *)(Qh + (size_t)row * p.q_rs + (idx % C8) * 8);
+            qpre[i] = *(const v4u *)(Qh + (size_t)row * p.q_rs + (idx % C8) * 8);
         }
         if (tid < QT) {
             const int row = i0 + tid;
@@ -364,7 +440,7 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
             const int idx = tid + NT * i;
-            *(uint4 *)(&ldsQ[buf][(idx / C8) * QROW + (idx % C8) * 8]) = qpre[i];
+            *(v4u *)(&ldsQ[buf][(idx / C8) * QROW + (idx % C8) * 8]) = qpre[i];
         }
         if (tid < QT) ldsL[buf][tid] = lpre;
     };
@@ -389,7 +465,7 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
                     for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const uint4 b = *(const uint4 *)(&ldsQ[buf][(qb * 32 + ln) * QROW + ks * 16 + 8 * lg]);
+                    const v4u b = *(const v4u *)(&ldsQ[buf][(qb * 32 + ln) * QROW + ks * 16 + 8 * lg]);
 #pragma unroll
                     for (int kb = 0; kb < KB; ++kb) s[kb] = mfma32(kreg[kb][ks], b, s[kb]);
                 }
@@ -432,19 +508,19 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
 
 // ------------------------------------------------------------------------------------------
 // Host-side launchers (called from the C-ABI file).
-template <int D, int QB, int NW>
+template <int D>
 static hipError_t launch_fwd(AttnParams p, hipStream_t st)
 {
-    constexpr int WROWS = 32 * QB;
+    constexpr int NW = kFwdWaves;
     int gp = 1;
-    if (p.G % 4 == 0 && NW % 4 == 0) gp = 4;
-    else if (p.G % 2 == 0 && NW % 2 == 0) gp = 2;
+    if (p.G % 4 == 0) gp = 4;
+    else if (p.G % 2 == 0) gp = 2;
     p.gp = gp;
-    const int rwg = (NW / gp) * WROWS;
+    const int rwg = (NW / gp) * 32;
     p.n_row_blocks = (p.Ct + rwg - 1) / rwg;
     const int grid = p.Hkv * (p.G / gp) * p.n_row_blocks;
-    const size_t smem = sizeof(u16) * (2 * 64 * (D + 8) + 2 * D * (64 + 8));
-    auto kern = attn_fwd_bf16<D, QB, NW>;
+    const size_t smem = fwd_lds_bytes<D>();
+    auto kern = attn_fwd_bf16<D>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, st, p);
@@ -462,8 +538,8 @@ static hipError_t launch_score(AttnParams p, hipStream_t st)
 
 hipError_t attend_bf16_forward(const AttnParams &p, hipStream_t st)
 {
-    if (p.D == 128) return launch_fwd<128, 1, 8>(p, st);
-    return launch_fwd<64, 1, 8>(p, st);
+    if (p.D == 128) return launch_fwd<128>(p, st);
+    return launch_fwd<64>(p, st);
 }
 
 hipError_t attend_bf16_score(const AttnParams &p, hipStream_t st)

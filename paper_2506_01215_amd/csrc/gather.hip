@@ -64,8 +64,8 @@ __global__ __launch_bounds__(256) void sim_bf16_mfma(GatherParams p)
         f32x4 dot = {0.f, 0.f, 0.f, 0.f}, gram = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
         for (int ks = 0; ks < D / 32; ++ks) {
-            const bf16x8 a = as_bf16x8(*(const uint4 *)(src + ks * 32));
-            const bf16x8 b = as_bf16x8(*(const uint4 *)(qsrc + ks * 32));
+            const bf16x8 a = as_bf16x8(*(const v4u *)(src + ks * 32));
+            const bf16x8 b = as_bf16x8(*(const v4u *)(qsrc + ks * 32));
             dot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, dot, 0, 0, 0);
             gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, a, gram, 0, 0, 0);
         }
