@@ -367,16 +367,66 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 // LDS.  Per-lane partial column sums are kept for the whole pass and reduced across the 32
 // query lanes once at the end, in a fixed order: no atomics, bitwise reproducible, and two cache
 // rows with identical keys get identical scores.
+//
+// Per logit the VALU does one v_fma (scale and -lse folded), one v_exp and one v_add; the mask is
+// applied only on the tiles that straddle the causal diagonal (separate, rarely taken path), and
+// rows outside the observation window or past the chunk end are switched off through lse = +inf.
+template <int D, int NT>
+struct QStage {
+    static constexpr int QT = 64;
+    static constexpr int QROW = D + 8;
+    static constexpr int C8 = D / 8;
+    static constexpr int PIECES = QT * C8 / NT;
+    static_assert(PIECES >= 1, "tile/threads mismatch");
+    v4u qpre[PIECES];
+    float lpre;
+    uint32_t goff, gstep;     // byte offset of this thread's first piece inside a tile, step per piece
+    uint32_t loff;            // element offset inside the LDS tile
+    int row0;
+
+    __device__ __forceinline__ void init(int tid, long q_rs)
+    {
+        row0 = tid / C8;
+        goff = (uint32_t)((long)row0 * q_rs * 2 + (tid % C8) * 16);
+        gstep = (uint32_t)((long)(NT / C8) * q_rs * 2);
+        loff = (uint32_t)(row0 * QROW + (tid % C8) * 8);
+        lpre = 0.f;
+    }
+    // Qt: first row of the tile (uniform); lse_t: lse of that row; rows_left = Ct - i0 (>= 1);
+    // first_obs = first observing row relative to the tile (<= 0 when the whole tile observes)
+    __device__ __forceinline__ void load(const u16 *Qt, const float *lse_t, int rows_left, int first_obs,
+                                         long q_rs, int tid)
+    {
+        const char *qb = (const char *)Qt;
+        if (rows_left >= QT) {
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) qpre[i] = *(const v4u *)(qb + (goff + gstep * (uint32_t)i));
+        } else {
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                int r = row0 + i * (NT / C8);
+                r = r < rows_left ? r : rows_left - 1;
+                qpre[i] = *(const v4u *)(qb + ((size_t)r * q_rs * 2 + (tid % C8) * 16));
+            }
+        }
+        if (tid < QT)
+            lpre = (tid >= first_obs && tid < rows_left) ? lse_t[tid] * kLog2e : INFINITY;
+    }
+    __device__ __forceinline__ void store(u16 *dq, float *dl, int tid) const
+    {
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) *(v4u *)(dq + loff + i * (NT / C8) * QROW) = qpre[i];
+        if (tid < QT) dl[tid] = lpre;
+    }
+};
+
 template <int D, int KB, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
+__global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
 {
     constexpr int NT = NW * 64;
     constexpr int KS = D / 16;
-    constexpr int QT = 64;               // query rows per LDS tile
-    constexpr int QROW = D + 8;
-    constexpr int C8 = D / 8;
-    constexpr int PIECES = QT * C8 / NT;
-    static_assert(PIECES >= 1, "tile/threads mismatch");
+    using Stage = QStage<D, NT>;
+    constexpr int QT = Stage::QT, QROW = Stage::QROW;
     constexpr int WKEYS = 32 * KB;
 
     __shared__ __attribute__((aligned(16))) u16 ldsQ[2][QT * QROW];
@@ -416,37 +466,18 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
     const int ntq = (p.Ct + QT - 1) / QT - qt0;          // q tiles per head (>= 1 since j_wg < n)
     const int iters = p.G * ntq;
     const float c = p.scale * kLog2e;
+    const int q_frag0 = ln * QROW + 8 * lg;
 
-    v4u qpre[PIECES];
-    float lpre = 0.f;
+    Stage st;
+    st.init(tid, p.q_rs);
     auto load_q = [&](int it) {
-        const int hh = it / ntq;
+        const int head = kvh * p.G + it / ntq;
         const int i0 = (qt0 + it % ntq) * QT;
-        const int head = kvh * p.G + hh;
-        const u16 *Qh = (const u16 *)p.q + (size_t)head * p.q_hs;
-#pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
-            const int idx = tid + NT * i;
-            int row = i0 + idx / C8;
-            row = row < p.Ct ? row : p.Ct - 1;
-            qpre[i] = *(const v4u *)(Qh + (size_t)row * p.q_rs + (idx % C8) * 8);
-        }
-        if (tid < QT) {
-            const int row = i0 + tid;
-            lpre = (row >= i_lo && row < p.Ct) ? p.lse[(size_t)head * p.Ct + row] * kLog2e : INFINITY;
-        }
+        st.load((const u16 *)p.q + (size_t)head * p.q_hs + (size_t)i0 * p.q_rs,
+                p.lse + (size_t)head * p.Ct + i0, p.Ct - i0, i_lo - i0, p.q_rs, tid);
     };
-    auto store_q = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
-            const int idx = tid + NT * i;
-            *(v4u *)(&ldsQ[buf][(idx / C8) * QROW + (idx % C8) * 8]) = qpre[i];
-        }
-        if (tid < QT) ldsL[buf][tid] = lpre;
-    };
-
     load_q(0);
-    store_q(0);
+    st.store(ldsQ[0], ldsL[0], tid);
     if (iters > 1) load_q(1);
     __syncthreads();
 
@@ -454,39 +485,65 @@ __global__ __launch_bounds__(NW * 64) void attn_score_bf16(AttnParams p)
         const int buf = it & 1;
         const int i0 = (qt0 + it % ntq) * QT;
         if (jw < p.n) {
+            const u16 *sq = ldsQ[buf] + q_frag0;
+            if (jw + WKEYS - 1 <= p.M + i0) {
+                // ---- every row of the tile sees every key of this wave
+                v4u bq[2][KS];
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const int r0 = i0 + qb * 32;                 // first row of this 32-row block
-                if (jw > p.M + r0 + 31) continue;            // no row of the block sees any key
-                f32x16 s[KB];
+                for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
+                    for (int ks = 0; ks < KS; ++ks) bq[qb][ks] = *(const v4u *)(sq + qb * 32 * QROW + ks * 16);
+                const float ls0 = ldsL[buf][ln], ls1 = ldsL[buf][32 + ln];
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+                for (int qb = 0; qb < 2; ++qb) {
+                    f32x16 s[KB];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const v4u b = *(const v4u *)(&ldsQ[buf][(qb * 32 + ln) * QROW + ks * 16 + 8 * lg]);
+                    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                    for (int kb = 0; kb < KB; ++kb) s[kb] = mfma32(kreg[kb][ks], b, s[kb]);
+                        for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) s[kb] = mfma32(kreg[kb][ks], bq[qb][ks], s[kb]);
+                    const float ls = qb ? ls1 : ls0;
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            col[kb][e] += __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -ls));
                 }
-                const float ls = ldsL[buf][qb * 32 + ln];
-                const bool need_mask = jw + WKEYS - 1 > p.M + r0;
-                const int lim = p.M + r0 + ln - jw;          // key offset <= lim is visible
+            } else {
+                asm volatile("; diagonal path" ::: "memory");
+#pragma unroll 1
+                for (int qb = 0; qb < 2; ++qb) {
+                    const int r0 = i0 + qb * 32;                 // first row of this 32-row block
+                    if (jw > p.M + r0 + 31) continue;            // no row of the block sees any key
+                    f32x16 s[KB];
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
+                    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -ls));
-                        if (need_mask) {
-                            const int koff = kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
-                            pv = koff > lim ? 0.f : pv;
-                        }
-                        col[kb][e] += pv;
+                        for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        const v4u b = *(const v4u *)(sq + qb * 32 * QROW + ks * 16);
+#pragma unroll
+                        for (int kb = 0; kb < KB; ++kb) s[kb] = mfma32(kreg[kb][ks], b, s[kb]);
                     }
+                    const float ls = ldsL[buf][qb * 32 + ln];
+                    const int lim = p.M + r0 + ln - jw;          // key offset <= lim is visible
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int koff = kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
+                            const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -ls));
+                            col[kb][e] += koff > lim ? 0.f : pv;
+                        }
+                }
             }
         }
         if (it + 1 < iters) {
-            store_q(buf ^ 1);
+            st.store(ldsQ[buf ^ 1], ldsL[buf ^ 1], tid);
             if (it + 2 < iters) load_q(it + 2);
         }
         __syncthreads();
