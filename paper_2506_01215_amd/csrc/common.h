@@ -32,12 +32,31 @@ struct AttnParams {
     int n_row_blocks;
 };
 
+// Top-k selection problem: nq rows of N candidates (row stride ld), k winners per row.
+struct SelParams {
+    const float *vals;
+    long ld, N;
+    int nq, k;
+    int n_sink, n_recent;    // first / last slots that are always selected (count inside k)
+    int *hist;               // [nq][3][2048]
+    uint32_t *sel_prefix;    // [3][nq]  selection state after each radix pass
+    int *sel_krem;           // [3][nq]
+    int *blk_cnt;            // [nq][nblk][2]   (above, equal) per workgroup
+    int nblk;                // ceil(N / 4096)
+    int32_t *out_idx;        // [nq][out_ld], ascending
+    float *out_val;          // nullable, values of the selected candidates
+    long out_ld;
+};
+
 struct EvictParams {
     void *k, *v;
     float *score;
     int32_t *pos;
     int32_t *kept;      // [Hkv][B]
     void *stage_k, *stage_v;   // [Hkv][B][row_bytes]
+    float *stage_score;        // [Hkv][B]
+    int32_t *stage_pos;        // [Hkv][B]
+    SelParams sel;             // top-B over score
     int Hkv, n, B, cap, n_sink, n_recent;
     int row_bytes;      // head_dim * sizeof(element), multiple of 16
 };
@@ -49,16 +68,11 @@ struct GatherParams {
     float *topk_score;   // nullable
     int32_t *union_idx;  // nullable
     int32_t *union_count;
-    // workspace pieces
-    int *hist;           // [nq][3][2048]
-    uint32_t *sel_prefix;   // [nq]
-    int *sel_krem;       // [nq]
-    int *blk_cnt;        // [nq][nblk][2]   (gt, eq)
+    SelParams sel;       // per-query top-k over sim
     uint32_t *bitmap;    // [nwords]
     int *word_cnt;       // [n_union_blocks]
     long N;
     int D, nq, k, radius, n_head, n_tail;
-    int nblk;            // selection blocks per query
     int nwords;          // bitmap words
     float eps;
     int q0, nq_grp;      // query group handled by this similarity launch
@@ -105,6 +119,31 @@ __device__ __forceinline__ uint32_t ordered_key(float f)
     uint32_t u = __float_as_uint(f);
     if (u == 0x80000000u) u = 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive scan of one int per thread over a 256-thread workgroup (tmp: 4 ints of LDS);
+// returns the exclusive prefix, `total` receives the workgroup sum.
+__device__ __forceinline__ int block256_excl_scan(int x, int *tmp, int &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(incl, o);
+        if (lane >= o) incl += y;
+    }
+    __syncthreads();
+    if (lane == 63) tmp[wave] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int t = tmp[w];
+        if (w < wave) base += t;
+        tot += t;
+    }
+    total = tot;
+    return base + incl - x;
 }
 
 }  // namespace reform

@@ -82,7 +82,7 @@ reform_status check_gather(const reform_gather_desc *d)
     if (d->n_query > 65535) return REFORM_ERR_UNSUPPORTED;
     const int grp = d->n_query < 16 ? d->n_query : 16;
     if ((size_t)grp * d->dim * 4 > 150 * 1024 && !(d->dtype == REFORM_BF16 && d->dim % 32 == 0 &&
-                                                     (size_t)16 * (d->dim + 8) * 2 <= 150 * 1024))
+                                                     (size_t)16 * (d->dim + 128) * 2 <= 150 * 1024))
         return REFORM_ERR_UNSUPPORTED;
     return REFORM_OK;
 }
@@ -101,8 +101,8 @@ GatherLayout gather_layout(const reform_gather_desc *d)
     size_t off = 0;
     L.sim = off;    off += align_up((size_t)d->n_query * d->n_ctx * sizeof(float));
     L.hist = off;   off += align_up((size_t)d->n_query * 3 * 2048 * sizeof(int));
-    L.prefix = off; off += align_up((size_t)d->n_query * sizeof(uint32_t));
-    L.krem = off;   off += align_up((size_t)d->n_query * sizeof(int));
+    L.prefix = off; off += align_up((size_t)3 * d->n_query * sizeof(uint32_t));
+    L.krem = off;   off += align_up((size_t)3 * d->n_query * sizeof(int));
     L.blk = off;    off += align_up((size_t)d->n_query * L.nblk * 2 * sizeof(int));
     L.bitmap = off; off += align_up((size_t)L.nwords * sizeof(uint32_t));
     L.words = off;  off += align_up((size_t)L.nublk * sizeof(int));
@@ -175,11 +175,35 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *d, const void *q
 }
 
 // ---------------------------------------------------------------------------------------
+struct EvictLayout {
+    size_t kept, stage_k, stage_v, stage_score, stage_pos, hist, prefix, krem, blk, total;
+    int nblk;
+};
+
+static EvictLayout evict_layout(const reform_evict_desc *d)
+{
+    EvictLayout L;
+    const size_t rows = (size_t)d->n_kv_heads * d->budget;
+    const size_t row_bytes = (size_t)d->head_dim * elt_size(d->dtype);
+    L.nblk = (d->n_valid + 4095) / 4096;
+    size_t off = 0;
+    L.kept = off;        off += align_up(rows * sizeof(int32_t));
+    L.stage_k = off;     off += align_up(rows * row_bytes);
+    L.stage_v = off;     off += align_up(rows * row_bytes);
+    L.stage_score = off; off += align_up(rows * sizeof(float));
+    L.stage_pos = off;   off += align_up(rows * sizeof(int32_t));
+    L.hist = off;        off += align_up((size_t)d->n_kv_heads * 3 * 2048 * sizeof(int));
+    L.prefix = off;      off += align_up((size_t)3 * d->n_kv_heads * sizeof(uint32_t));
+    L.krem = off;        off += align_up((size_t)3 * d->n_kv_heads * sizeof(int));
+    L.blk = off;         off += align_up((size_t)d->n_kv_heads * (L.nblk ? L.nblk : 1) * 2 * sizeof(int));
+    L.total = off;
+    return L;
+}
+
 size_t reform_evict_topk_compact_workspace(const reform_evict_desc *d)
 {
     if (check_evict(d) != REFORM_OK) return 0;
-    const size_t rows = (size_t)d->n_kv_heads * d->budget;
-    return align_up(rows * sizeof(int32_t)) + 2 * align_up(rows * d->head_dim * elt_size(d->dtype));
+    return evict_layout(d).total;
 }
 
 reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, void *v, float *score,
@@ -196,19 +220,30 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, voi
             return REFORM_ERR_RUNTIME;
         return REFORM_OK;
     }
-    const size_t need = reform_evict_topk_compact_workspace(d);
-    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & (kAlign - 1)))
+    const EvictLayout L = evict_layout(d);
+    if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & (kAlign - 1)))
         return REFORM_ERR_WORKSPACE;
-    const size_t rows = (size_t)d->n_kv_heads * d->budget;
     char *ws = (char *)workspace;
     EvictParams p;
+    std::memset(&p, 0, sizeof(p));
     p.k = k; p.v = v; p.score = score; p.pos = pos;
-    p.kept = kept_idx ? kept_idx : (int32_t *)ws;
-    p.stage_k = ws + align_up(rows * sizeof(int32_t));
-    p.stage_v = (char *)p.stage_k + align_up(rows * d->head_dim * elt_size(d->dtype));
+    p.kept = kept_idx ? kept_idx : (int32_t *)(ws + L.kept);
+    p.stage_k = ws + L.stage_k;
+    p.stage_v = ws + L.stage_v;
+    p.stage_score = (float *)(ws + L.stage_score);
+    p.stage_pos = (int32_t *)(ws + L.stage_pos);
     p.Hkv = d->n_kv_heads; p.n = d->n_valid; p.B = d->budget; p.cap = d->capacity;
     p.n_sink = d->n_sink; p.n_recent = d->n_recent;
     p.row_bytes = (int)(d->head_dim * elt_size(d->dtype));
+    p.sel.vals = score; p.sel.ld = d->capacity; p.sel.N = d->n_valid;
+    p.sel.nq = d->n_kv_heads; p.sel.k = d->budget;
+    p.sel.n_sink = d->n_sink; p.sel.n_recent = d->n_recent;
+    p.sel.hist = (int *)(ws + L.hist);
+    p.sel.sel_prefix = (uint32_t *)(ws + L.prefix);
+    p.sel.sel_krem = (int *)(ws + L.krem);
+    p.sel.blk_cnt = (int *)(ws + L.blk);
+    p.sel.nblk = L.nblk;
+    p.sel.out_idx = p.kept; p.sel.out_val = nullptr; p.sel.out_ld = d->budget;
     return evict_run(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 
@@ -259,13 +294,18 @@ reform_status reform_gather_topk(const reform_gather_desc *d, const void *emb, c
     p.sim = (float *)(ws + L.sim);
     p.topk_idx = topk_idx; p.topk_score = topk_score;
     p.union_idx = union_idx; p.union_count = union_count;
-    p.hist = (int *)(ws + L.hist);
-    p.sel_prefix = (uint32_t *)(ws + L.prefix);
-    p.sel_krem = (int *)(ws + L.krem);
-    p.blk_cnt = (int *)(ws + L.blk);
     p.bitmap = (uint32_t *)(ws + L.bitmap);
     p.word_cnt = (int *)(ws + L.words);
-    p.nblk = L.nblk; p.nwords = L.nwords;
+    p.nwords = L.nwords;
+    p.sel.vals = p.sim; p.sel.ld = d->n_ctx; p.sel.N = d->n_ctx;
+    p.sel.nq = d->n_query; p.sel.k = d->k;
+    p.sel.n_sink = 0; p.sel.n_recent = 0;
+    p.sel.hist = (int *)(ws + L.hist);
+    p.sel.sel_prefix = (uint32_t *)(ws + L.prefix);
+    p.sel.sel_krem = (int *)(ws + L.krem);
+    p.sel.blk_cnt = (int *)(ws + L.blk);
+    p.sel.nblk = L.nblk;
+    p.sel.out_idx = topk_idx; p.sel.out_val = topk_score; p.sel.out_ld = d->k;
     hipStream_t st = (hipStream_t)hip_stream;
     if (gather_similarity(p, d->dtype == REFORM_BF16, st) != hipSuccess) return REFORM_ERR_RUNTIME;
     return gather_select_union(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
