@@ -57,6 +57,8 @@ struct EvictParams {
     float *stage_score;        // [Hkv][B]
     int32_t *stage_pos;        // [Hkv][B]
     SelParams sel;             // top-B over score
+    int *sync;                 // in-place move: [0] ticket, [1] error, [2..] per-tile flags; null = staged move
+    int ntile;                 // tiles per stream of the in-place move
     int Hkv, n, B, cap, n_sink, n_recent;
     int row_bytes;      // head_dim * sizeof(element), multiple of 16
 };

@@ -4,8 +4,10 @@
 //
 //   select_topk    (select.hip) exact top-B of the n candidate scores per KV head, lowest-index
 //                  ties, protected first/last slots, kept slot indices ascending
-//   evict_move<true>   K, V rows and the score / pos entries of the kept slots -> staging
-//   evict_move<false>  staging -> rows [0, new_len)
+//   evict_move_inplace K and V rows of the kept slots -> rows [0, new_len), one read + one write
+//                      per moved row, ordered by per-tile flags (row sizes dividing 16 KB)
+//   evict_move_side    the 4-byte score / pos entries through a small staging buffer
+//   evict_move<..>     fallback for other row sizes: K, V, score, pos through staging
 // Rows whose slot does not change (kept_idx[r] == r, always a prefix) are not touched.
 #include "common.h"
 
@@ -57,11 +59,145 @@ __global__ __launch_bounds__(256) void evict_move(EvictParams p)
     else *(v4u *)cache = *(const v4u *)stage;
 }
 
+// grid (ceil(B/256), Hkv): the 4-byte score and pos entries only.
+template <bool TO_STAGE>
+__global__ __launch_bounds__(256) void evict_move_side(EvictParams p)
+{
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    const int g = blockIdx.y;
+    if (r >= p.B) return;
+    const int src = p.kept[(size_t)g * p.B + r];
+    if (src == r || (unsigned)src >= (unsigned)p.n) return;
+    const size_t srow = (size_t)g * p.cap + (TO_STAGE ? src : r);
+    const size_t trow = (size_t)g * p.B + r;
+    if (TO_STAGE) {
+        p.stage_score[trow] = p.score[srow];
+        if (p.pos) p.stage_pos[trow] = p.pos[srow];
+    } else {
+        p.score[srow] = p.stage_score[trow];
+        if (p.pos) p.pos[srow] = p.stage_pos[trow];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// In-place, single-pass compaction of the K and V rows.  Destination row r takes source row
+// kept[r] >= r, so a workgroup that writes dest rows [a, b) may destroy sources that other
+// workgroups still have to read.  Who reads the rows [a, b)?  The dest rows rank(a)..rank(b)-1
+// (rank(x) = number of kept slots below x), which lie in at most two tiles, both at or before the
+// writer's own tile.  Protocol per tile of 16 KB:
+//   1. take a ticket (atomic counter): tiles of one stream (head, K|V) are handed out in ascending
+//      order, so every lower tile of the stream is already running when a tile starts;
+//   2. load the tile's source rows into registers and wait until the data has arrived;
+//   3. publish flag[stream][tile] = 1 (release);
+//   4. wait (acquire) for the flags of the <= 2 tiles that read rows [a, b) -- they never wait
+//      before publishing, so this ends; the spin is bounded anyway and a timeout only raises an
+//      error word;
+//   5. store the registers to rows [a, b).
+// Traffic: every moved row is read once and written once.
+constexpr int kTileBytes = 16384;
+constexpr int kSpinLimit = 1 << 22;
+
+__global__ void evict_sync_zero(int *sync, int count)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) sync[i] = 0;
+}
+
+__global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
+{
+    __shared__ int sh[4];
+    const int tid = threadIdx.x;
+    const int nstreams = p.Hkv * 2;
+    const int tr = kTileBytes / p.row_bytes;             // rows per tile
+    const int pieces = p.row_bytes >> 4;
+    int *counter = p.sync;                                // [0] ticket, [1] error, [2..] flags
+    int *flags = p.sync + 2;
+    if (tid == 0) sh[0] = atomicAdd(counter, 1);
+    __syncthreads();
+    const int ticket = sh[0];
+    const int stream = ticket % nstreams, tile = ticket / nstreams;
+    const int g = stream >> 1;
+    const int a = tile * tr, b = min(a + tr, p.B);
+    if (a >= p.B) return;
+    const int32_t *kept = p.kept + (size_t)g * p.B;
+    int *flag = flags + (size_t)stream * p.ntile;
+    char *base = (char *)((stream & 1) ? p.v : p.k) + (size_t)g * p.cap * p.row_bytes;
+
+    if (kept[b - 1] == b - 1) {                           // kept[r] == r for every r < b: nothing moves
+        if (tid == 0) __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    v4u data[4];
+    int rows[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = tid + 256 * i;
+        const int r = a + q / pieces, c = q % pieces;
+        rows[i] = r < b ? r : -1;
+        if (r < b) {
+            int src = kept[r];
+            src = (unsigned)src < (unsigned)p.n ? src : r;
+            data[i] = *(const v4u *)(base + (size_t)src * p.row_bytes + (size_t)c * 16);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);                        // all loads of this wave have returned
+    asm volatile("" ::: "memory");
+    __syncthreads();                                      // ... and of every wave of the tile
+    if (tid == 0) {
+        __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        // readers of rows [a, b): dest rows lo .. hi-1 with lo = rank(a), hi = rank(b)
+        int lo = 0, hi = p.B;
+        {
+            int l = 0, h = p.B;
+            while (l < h) { const int m = (l + h) >> 1; if (kept[m] < a) l = m + 1; else h = m; }
+            lo = l;
+            l = lo; h = p.B;
+            while (l < h) { const int m = (l + h) >> 1; if (kept[m] < b) l = m + 1; else h = m; }
+            hi = l;
+        }
+        if (hi > lo) {
+            for (int t2 = lo / tr; t2 <= (hi - 1) / tr; ++t2) {
+                if (t2 == tile) continue;
+                int spins = 0;
+                while (__hip_atomic_load(&flag[t2], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+                    if (++spins > kSpinLimit) { atomicExch(&counter[1], 1); break; }
+                    __builtin_amdgcn_s_sleep(4);
+                }
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (rows[i] >= 0) {
+            const int c = (tid + 256 * i) % pieces;
+            *(v4u *)(base + (size_t)rows[i] * p.row_bytes + (size_t)c * 16) = data[i];
+        }
+    }
+}
+
 hipError_t evict_run(const EvictParams &p, hipStream_t st)
 {
     hipError_t e = select_topk(p.sel, st);
     if (e != hipSuccess) return e;
-    const long items = (long)p.B * (p.row_bytes >> 4);
+    const int pieces = p.row_bytes >> 4;
+    if (p.sync) {
+        // side entries through staging (8 bytes per row), K/V rows in place
+        const dim3 sgrid((unsigned)((p.B + 255) / 256), p.Hkv, 1);
+        hipLaunchKernelGGL(evict_move_side<true>, sgrid, dim3(256), 0, st, p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const int nsync = 2 + p.Hkv * 2 * p.ntile;
+        hipLaunchKernelGGL(evict_sync_zero, dim3((nsync + 255) / 256), dim3(256), 0, st, p.sync, nsync);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(evict_move_inplace, dim3(p.Hkv * 2 * p.ntile), dim3(256), 0, st, p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(evict_move_side<false>, sgrid, dim3(256), 0, st, p);
+        return hipGetLastError();
+    }
+    const long items = (long)p.B * pieces;
     const dim3 grid((unsigned)((items + 255) / 256), p.Hkv, 3);
     hipLaunchKernelGGL(evict_move<true>, grid, dim3(256), 0, st, p);
     e = hipGetLastError();

@@ -176,8 +176,9 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *d, const void *q
 
 // ---------------------------------------------------------------------------------------
 struct EvictLayout {
-    size_t kept, stage_k, stage_v, stage_score, stage_pos, hist, prefix, krem, blk, total;
-    int nblk;
+    size_t kept, stage_k, stage_v, stage_score, stage_pos, hist, prefix, krem, blk, sync, total;
+    int nblk, ntile;
+    bool inplace;
 };
 
 static EvictLayout evict_layout(const reform_evict_desc *d)
@@ -187,15 +188,19 @@ static EvictLayout evict_layout(const reform_evict_desc *d)
     const size_t row_bytes = (size_t)d->head_dim * elt_size(d->dtype);
     L.nblk = (d->n_valid + 4095) / 4096;
     size_t off = 0;
+    // rows whose size divides 16 KB move in place; other sizes go through K/V staging
+    L.inplace = row_bytes <= 16384 && (16384 % row_bytes) == 0;
+    L.ntile = L.inplace ? (int)(((size_t)d->budget * row_bytes + 16383) / 16384) : 0;
     L.kept = off;        off += align_up(rows * sizeof(int32_t));
-    L.stage_k = off;     off += align_up(rows * row_bytes);
-    L.stage_v = off;     off += align_up(rows * row_bytes);
+    L.stage_k = off;     off += L.inplace ? 0 : align_up(rows * row_bytes);
+    L.stage_v = off;     off += L.inplace ? 0 : align_up(rows * row_bytes);
     L.stage_score = off; off += align_up(rows * sizeof(float));
     L.stage_pos = off;   off += align_up(rows * sizeof(int32_t));
     L.hist = off;        off += align_up((size_t)d->n_kv_heads * 3 * 2048 * sizeof(int));
     L.prefix = off;      off += align_up((size_t)3 * d->n_kv_heads * sizeof(uint32_t));
     L.krem = off;        off += align_up((size_t)3 * d->n_kv_heads * sizeof(int));
     L.blk = off;         off += align_up((size_t)d->n_kv_heads * (L.nblk ? L.nblk : 1) * 2 * sizeof(int));
+    L.sync = off;        off += align_up((size_t)(2 + 2 * d->n_kv_heads * (L.ntile ? L.ntile : 1)) * sizeof(int));
     L.total = off;
     return L;
 }
@@ -244,6 +249,8 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, voi
     p.sel.blk_cnt = (int *)(ws + L.blk);
     p.sel.nblk = L.nblk;
     p.sel.out_idx = p.kept; p.sel.out_val = nullptr; p.sel.out_ld = d->budget;
+    p.sync = L.inplace ? (int *)(ws + L.sync) : nullptr;
+    p.ntile = L.ntile;
     return evict_run(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 

@@ -77,7 +77,9 @@ def test_evict_rejects_bad_arguments():
     assert call(mk(head_dim=4)) == 2                      # 8-byte rows
     assert call(mk()) == 3                                # eviction needed but no workspace
     need = lib.reform_evict_topk_compact_workspace(ctypes.byref(mk()))
-    assert need >= 8 * 100 * 4 + 2 * 8 * 100 * 256
+    assert need >= 8 * 100 * 4 + 2 * 8 * 100 * 4                 # kept indices + score/pos staging
+    odd = mk(head_dim=96)                                         # 192-byte rows do not divide 16 KB:
+    assert lib.reform_evict_topk_compact_workspace(ctypes.byref(odd)) >= 2 * 8 * 100 * 192   # K/V staging
     assert call(mk(), ctypes.c_void_p(0x1100), need - 1) == 3
     assert call(mk(), ctypes.c_void_p(0x1010), need) == 3  # misaligned
 

@@ -120,6 +120,12 @@ def test_optional_outputs_may_be_null():
     run_case(2, 64, 900, 400, 900, torch.bfloat16, rand_scores(2, 900, 2), with_pos=False, with_kept=False)
 
 
+def test_row_size_that_needs_the_staged_path():
+    """head_dim 96 bf16 = 192-byte rows: not a divisor of the 16 KB in-place tile."""
+    run_case(3, 96, 3000, 1000, 3010, torch.bfloat16, rand_scores(3, 3010, 8, ties=True), seed=4)
+    run_case(2, 24, 500, 200, 500, torch.float32, rand_scores(2, 500, 9), seed=5)
+
+
 def test_full_size_layer_step():
     """Workload 3's shape: 8 KV heads, 65536 candidates -> 32768, head_dim 128 bf16."""
     run_case(8, 128, 65536, 32768, 65536, torch.bfloat16, rand_scores(8, 65536, 77, ties=False), seed=3)
