@@ -46,6 +46,7 @@ struct SelParams {
     int32_t *out_idx;        // [nq][out_ld], ascending
     float *out_val;          // nullable, values of the selected candidates
     long out_ld;
+    int32_t *out_rank;       // nullable [nq][ld]: rank[t] = number of selected candidates below t
 };
 
 struct EvictParams {
@@ -57,7 +58,7 @@ struct EvictParams {
     float *stage_score;        // [Hkv][B]
     int32_t *stage_pos;        // [Hkv][B]
     SelParams sel;             // top-B over score
-    int *sync;                 // in-place move: [0] ticket, [1] error, [2..] per-tile flags; null = staged move
+    int *sync;                 // in-place move: error word, per-stream tickets, per-tile flags; null = staged move
     int ntile;                 // tiles per stream of the in-place move
     int Hkv, n, B, cap, n_sink, n_recent;
     int row_bytes;      // head_dim * sizeof(element), multiple of 16

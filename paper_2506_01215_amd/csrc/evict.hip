@@ -85,17 +85,22 @@ __global__ __launch_bounds__(256) void evict_move_side(EvictParams p)
 // workgroups still have to read.  Who reads the rows [a, b)?  The dest rows rank(a)..rank(b)-1
 // (rank(x) = number of kept slots below x), which lie in at most two tiles, both at or before the
 // writer's own tile.  Protocol per tile of 16 KB:
-//   1. take a ticket (atomic counter): tiles of one stream (head, K|V) are handed out in ascending
-//      order, so every lower tile of the stream is already running when a tile starts;
+//   1. take a ticket from the stream's atomic counter (stream = (head, K|V)): tiles of a stream are
+//      handed out in ascending order, so every lower tile of the stream is already running when a
+//      tile starts, whatever order the hardware dispatches workgroups in;
 //   2. load the tile's source rows into registers and wait until the data has arrived;
-//   3. publish flag[stream][tile] = 1 (release);
-//   4. wait (acquire) for the flags of the <= 2 tiles that read rows [a, b) -- they never wait
-//      before publishing, so this ends; the spin is bounded anyway and a timeout only raises an
-//      error word;
+//   3. publish flag[stream][tile] = 1 with a relaxed device-scope atomic store.  Nothing has to be
+//      made visible except the flag itself (the tile has only READ so far, and its loads have
+//      returned), so no release fence is used: on a multi-XCD part a device-scope release writes
+//      back a whole L2 and made this kernel 4x slower than the staged copy;
+//   4. poll (relaxed atomic loads) the flags of the <= 2 tiles that read rows [a, b) -- they never
+//      wait before publishing, so this ends; the spin is bounded anyway and a timeout only raises
+//      an error word.  The stores of step 5 are issued after the poll returned;
 //   5. store the registers to rows [a, b).
 // Traffic: every moved row is read once and written once.
 constexpr int kTileBytes = 16384;
 constexpr int kSpinLimit = 1 << 22;
+constexpr int kSyncLine = 32;        // ints per 128-byte line
 
 __global__ void evict_sync_zero(int *sync, int count)
 {
@@ -110,12 +115,14 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
     const int nstreams = p.Hkv * 2;
     const int tr = kTileBytes / p.row_bytes;             // rows per tile
     const int pieces = p.row_bytes >> 4;
-    int *counter = p.sync;                                // [0] ticket, [1] error, [2..] flags
-    int *flags = p.sync + 2;
+    // sync layout: [0] error word, then one ticket counter per stream (each on its own 128-byte
+    // line: a single shared counter serialises 8192 atomics on one L2 address), then the flags
+    const int stream = blockIdx.x % nstreams;
+    int *counter = p.sync + kSyncLine * (1 + stream);
+    int *flags = p.sync + kSyncLine * (1 + nstreams);
     if (tid == 0) sh[0] = atomicAdd(counter, 1);
     __syncthreads();
-    const int ticket = sh[0];
-    const int stream = ticket % nstreams, tile = ticket / nstreams;
+    const int tile = sh[0];                               // ascending within the stream
     const int g = stream >> 1;
     const int a = tile * tr, b = min(a + tr, p.B);
     if (a >= p.B) return;
@@ -124,7 +131,7 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
     char *base = (char *)((stream & 1) ? p.v : p.k) + (size_t)g * p.cap * p.row_bytes;
 
     if (kept[b - 1] == b - 1) {                           // kept[r] == r for every r < b: nothing moves
-        if (tid == 0) __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     v4u data[4];
@@ -144,27 +151,21 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
     asm volatile("" ::: "memory");
     __syncthreads();                                      // ... and of every wave of the tile
     if (tid == 0) {
-        __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // readers of rows [a, b): dest rows lo .. hi-1 with lo = rank(a), hi = rank(b)
-        int lo = 0, hi = p.B;
-        {
-            int l = 0, h = p.B;
-            while (l < h) { const int m = (l + h) >> 1; if (kept[m] < a) l = m + 1; else h = m; }
-            lo = l;
-            l = lo; h = p.B;
-            while (l < h) { const int m = (l + h) >> 1; if (kept[m] < b) l = m + 1; else h = m; }
-            hi = l;
-        }
+        const int32_t *rank = p.sel.out_rank + (size_t)g * p.cap;
+        const int lo = rank[a], hi = rank[b];             // b <= B < n: inside the candidate range
         if (hi > lo) {
             for (int t2 = lo / tr; t2 <= (hi - 1) / tr; ++t2) {
                 if (t2 == tile) continue;
                 int spins = 0;
-                while (__hip_atomic_load(&flag[t2], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-                    if (++spins > kSpinLimit) { atomicExch(&counter[1], 1); break; }
+                while (__hip_atomic_load(&flag[t2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+                    if (++spins > kSpinLimit) { atomicExch(p.sync, 1); break; }
                     __builtin_amdgcn_s_sleep(4);
                 }
             }
         }
+        asm volatile("" ::: "memory");
     }
     __syncthreads();
 #pragma unroll
@@ -187,7 +188,7 @@ hipError_t evict_run(const EvictParams &p, hipStream_t st)
         hipLaunchKernelGGL(evict_move_side<true>, sgrid, dim3(256), 0, st, p);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        const int nsync = 2 + p.Hkv * 2 * p.ntile;
+        const int nsync = kSyncLine * (1 + p.Hkv * 2) + p.Hkv * 2 * p.ntile;
         hipLaunchKernelGGL(evict_sync_zero, dim3((nsync + 255) / 256), dim3(256), 0, st, p.sync, nsync);
         e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -176,7 +176,7 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *d, const void *q
 
 // ---------------------------------------------------------------------------------------
 struct EvictLayout {
-    size_t kept, stage_k, stage_v, stage_score, stage_pos, hist, prefix, krem, blk, sync, total;
+    size_t kept, stage_k, stage_v, stage_score, stage_pos, hist, prefix, krem, blk, sync, rank, total;
     int nblk, ntile;
     bool inplace;
 };
@@ -200,7 +200,8 @@ static EvictLayout evict_layout(const reform_evict_desc *d)
     L.prefix = off;      off += align_up((size_t)3 * d->n_kv_heads * sizeof(uint32_t));
     L.krem = off;        off += align_up((size_t)3 * d->n_kv_heads * sizeof(int));
     L.blk = off;         off += align_up((size_t)d->n_kv_heads * (L.nblk ? L.nblk : 1) * 2 * sizeof(int));
-    L.sync = off;        off += align_up((size_t)(2 + 2 * d->n_kv_heads * (L.ntile ? L.ntile : 1)) * sizeof(int));
+    L.sync = off;        off += align_up((size_t)(32 * (1 + 2 * d->n_kv_heads) + 2 * d->n_kv_heads * (L.ntile ? L.ntile : 1)) * sizeof(int));
+    L.rank = off;        off += L.inplace ? align_up((size_t)d->n_kv_heads * d->capacity * sizeof(int32_t)) : 0;
     L.total = off;
     return L;
 }
@@ -249,6 +250,7 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, voi
     p.sel.blk_cnt = (int *)(ws + L.blk);
     p.sel.nblk = L.nblk;
     p.sel.out_idx = p.kept; p.sel.out_val = nullptr; p.sel.out_ld = d->budget;
+    p.sel.out_rank = L.inplace ? (int32_t *)(ws + L.rank) : nullptr;
     p.sync = L.inplace ? (int *)(ws + L.sync) : nullptr;
     p.ntile = L.ntile;
     return evict_run(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;

@@ -178,12 +178,14 @@ __global__ __launch_bounds__(256) void select_write(SelParams p)
     const int kept_before_blk = base_gt + min(base_eq, need_eq);
     int dest = kept_before_blk + block256_excl_scan(gt_c + eq_take, tmp, tot);
     int eq_seen = eq_before;
+    int32_t *orank = p.out_rank ? p.out_rank + (size_t)q * p.ld : nullptr;
     int32_t *oi = p.out_idx + (size_t)q * p.out_ld;
     float *os = p.out_val ? p.out_val + (size_t)q * p.out_ld : nullptr;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const long t = t0 + i;
         if (t >= p.N) break;
+        if (orank) orank[t] = dest;
         bool keep = u[i] > T;
         if (u[i] == T) { keep = eq_seen < need_eq; ++eq_seen; }
         if (keep && dest < p.k) {
