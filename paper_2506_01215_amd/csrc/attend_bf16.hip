@@ -131,7 +131,10 @@ __device__ __forceinline__ float dot2_ones(uint32_t packed, float acc)
 }
 
 // p = exp2(s*c - mc) for the 32 logits a lane holds of one 64-key tile, packed to bf16 as the four
-// B operands of P.V; returns the lane's partial row sum of the ROUNDED probabilities.
+// B operands of P.V; returns the lane's partial row sum.  The sum uses plain v_add_f32 on purpose:
+// v_dot2c_f32_bf16 (two per instruction) was measured NOT to co-execute with another wave's MFMAs
+// on gfx950 (a wave of cvt+dot2 next to a wave of MFMAs takes the sum of their solo times), while
+// v_fma / v_add / v_exp / v_cvt_pk do overlap almost completely.
 __device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, float mc, v4u (&pb)[4])
 {
     float rs = 0.f;
@@ -139,7 +142,10 @@ __device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, flo
     for (int kb = 0; kb < 2; ++kb) {
         float pv[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -mc));
+        for (int e = 0; e < 16; ++e) {
+            pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -mc));
+            rs += pv[e];
+        }
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
             v4u w;
@@ -147,10 +153,6 @@ __device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, flo
             w.y = pack_bf16x2(pv[8 * hh + 2], pv[8 * hh + 3]);
             w.z = pack_bf16x2(pv[8 * hh + 4], pv[8 * hh + 5]);
             w.w = pack_bf16x2(pv[8 * hh + 6], pv[8 * hh + 7]);
-            rs = dot2_ones(w.x, rs);
-            rs = dot2_ones(w.y, rs);
-            rs = dot2_ones(w.z, rs);
-            rs = dot2_ones(w.w, rs);
             pb[kb * 2 + hh] = w;
         }
     }
@@ -170,8 +172,6 @@ __device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, flo
 //     m_run; if a row outgrew it by more than kBigSum (or m_run is still -inf) the tile sum of
 //     that row is huge / inf / NaN, and only then the whole wave recomputes with the true maximum
 //     and rescales its 16*DB accumulators once;
-//   - the row sum comes from the bf16-rounded probabilities with v_dot2 (two per instruction),
-//     i.e. from exactly the weights that multiply V;
 //   - scale*log2(e) folded into one v_fma per logit, v_exp_f32 directly, packed bf16 converts;
 //   - tile addresses are a uniform base plus per-thread constants computed once.
 constexpr float kBigSum = 65536.0f;
@@ -380,6 +380,7 @@ struct QStage {
     static_assert(PIECES >= 1, "tile/threads mismatch");
     v4u qpre[PIECES];
     float lpre;
+    bool lvalid;
     uint32_t goff, gstep;     // byte offset of this thread's first piece inside a tile, step per piece
     uint32_t loff;            // element offset inside the LDS tile
     int row0;
@@ -391,6 +392,7 @@ struct QStage {
         gstep = (uint32_t)((long)(NT / C8) * q_rs * 2);
         loff = (uint32_t)(row0 * QROW + (tid % C8) * 8);
         lpre = 0.f;
+        lvalid = false;
     }
     // Qt: first row of the tile (uniform); lse_t: lse of that row; rows_left = Ct - i0 (>= 1);
     // first_obs = first observing row relative to the tile (<= 0 when the whole tile observes)
@@ -409,14 +411,17 @@ struct QStage {
                 qpre[i] = *(const v4u *)(qb + ((size_t)r * q_rs * 2 + (tid % C8) * 16));
             }
         }
-        if (tid < QT)
-            lpre = (tid >= first_obs && tid < rows_left) ? lse_t[tid] * kLog2e : INFINITY;
+        // raw value only: multiplying here would wait for the load right after issuing it
+        if (tid < QT) {
+            lvalid = tid >= first_obs && tid < rows_left;
+            lpre = lvalid ? lse_t[tid] : 0.f;
+        }
     }
     __device__ __forceinline__ void store(u16 *dq, float *dl, int tid) const
     {
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) *(v4u *)(dq + loff + i * (NT / C8) * QROW) = qpre[i];
-        if (tid < QT) dl[tid] = lpre;
+        if (tid < QT) dl[tid] = lvalid ? lpre * kLog2e : INFINITY;
     }
 };
 
@@ -481,6 +486,45 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
     if (iters > 1) load_q(1);
     __syncthreads();
 
+    // Rotation inside a wave: the MFMAs of a 32-row block are interleaved, one MFMA to six
+    // VALU instructions, with the v_fma / v_exp / v_add work of the PREVIOUS block, which never
+    // waits for the MFMAs in flight (an MFMA occupies the matrix pipe for about as long as six
+    // such instructions take to issue).  `sB`/`lsB` carry the block whose VALU work is pending;
+    // lsB = +inf makes a block contribute exactly 0 (the empty state).
+    f32x16 sA[KB], sB[KB];                 // sB carries the pending block across iterations
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sB[kb][e] = 0.f;
+    float lsB = INFINITY;
+    auto issue_mfma = [&](f32x16 (&dst)[KB], const u16 *src) {
+        v4u bq[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bq[ks] = *(const v4u *)(src + ks * 16);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) dst[kb][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) dst[kb] = mfma32(kreg[kb][ks], bq[ks], dst[kb]);
+    };
+    auto accumulate = [&](const f32x16 (&src)[KB], float ls) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) col[kb][e] += __builtin_amdgcn_exp2f(fmaf(src[kb][e], c, -ls));
+    };
+
+    auto interleave_pattern = [&]() {
+        __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
+#pragma unroll
+        for (int u = 0; u < KS * KB; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA ...
+            __builtin_amdgcn_sched_group_barrier(0x402, 6, 0);     // ... then six VALU/transcendental ops
+        }
+    };
     for (int it = 0; it < iters; ++it) {
         const int buf = it & 1;
         const int i0 = (qt0 + it % ntq) * QT;
@@ -488,47 +532,25 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
             const u16 *sq = ldsQ[buf] + q_frag0;
             if (jw + WKEYS - 1 <= p.M + i0) {
                 // ---- every row of the tile sees every key of this wave
-                v4u bq[2][KS];
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) bq[qb][ks] = *(const v4u *)(sq + qb * 32 * QROW + ks * 16);
                 const float ls0 = ldsL[buf][ln], ls1 = ldsL[buf][32 + ln];
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    f32x16 s[KB];
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                        for (int kb = 0; kb < KB; ++kb) s[kb] = mfma32(kreg[kb][ks], bq[qb][ks], s[kb]);
-                    const float ls = qb ? ls1 : ls0;
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            col[kb][e] += __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -ls));
-                }
+                issue_mfma(sA, sq);
+                accumulate(sB, lsB);
+                interleave_pattern();
+                __builtin_amdgcn_sched_barrier(0);
+                issue_mfma(sB, sq + 32 * QROW);
+                accumulate(sA, ls0);
+                interleave_pattern();
+                __builtin_amdgcn_sched_barrier(0);
+                lsB = ls1;
             } else {
                 asm volatile("; diagonal path" ::: "memory");
+                accumulate(sB, lsB);                  // flush the pending block first
+                lsB = INFINITY;
 #pragma unroll 1
                 for (int qb = 0; qb < 2; ++qb) {
                     const int r0 = i0 + qb * 32;                 // first row of this 32-row block
                     if (jw > p.M + r0 + 31) continue;            // no row of the block sees any key
-                    f32x16 s[KB];
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        const v4u b = *(const v4u *)(sq + qb * 32 * QROW + ks * 16);
-#pragma unroll
-                        for (int kb = 0; kb < KB; ++kb) s[kb] = mfma32(kreg[kb][ks], b, s[kb]);
-                    }
+                    issue_mfma(sA, sq + qb * 32 * QROW);
                     const float ls = ldsL[buf][qb * 32 + ln];
                     const int lim = p.M + r0 + ln - jw;          // key offset <= lim is visible
 #pragma unroll
@@ -536,7 +558,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
 #pragma unroll
                         for (int e = 0; e < 16; ++e) {
                             const int koff = kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
-                            const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -ls));
+                            const float pv = __builtin_amdgcn_exp2f(fmaf(sA[kb][e], c, -ls));
                             col[kb][e] += koff > lim ? 0.f : pv;
                         }
                 }
@@ -548,6 +570,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
         }
         __syncthreads();
     }
+    accumulate(sB, lsB);                       // flush the last pending block
 
     if (jw >= p.n) return;
     float *dst = p.score + (size_t)kvh * p.cap;
@@ -601,7 +624,7 @@ hipError_t attend_bf16_forward(const AttnParams &p, hipStream_t st)
 
 hipError_t attend_bf16_score(const AttnParams &p, hipStream_t st)
 {
-    if (p.D == 128) return launch_score<128, 2, 4>(p, st);
+    if (p.D == 128) return launch_score<128, 2, 8>(p, st);
     return launch_score<64, 2, 4>(p, st);
 }
 
