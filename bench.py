@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# HBM bytes one attn_fwd_bf16 launch of the default workload moves, from the two rocprofv3 --pmc
+# runs summarised in profiles/attn_fwd_cfg3_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE in KiB per
+# dispatch, each scaled by what the same counter reads for a 1 GiB copy kernel: x2.000 and x1.000).
+FWD_TRAFFIC_BYTES = (1736800 * 2.000 + 266240 * 1.000) * 1024
 
 
 def parse():
@@ -32,6 +36,12 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="debug only: fewer layers (marks the result invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true")
+    ap.add_argument("--zero-data", action="store_true",
+                    help="debug only: all-zero Q/K/V (marks the result invalid); shows how much of the "
+                         "kernel time is the power-limited clock that random operands cause")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed region, run a plain 1 GiB -> 1 GiB elementwise copy kernel; "
+                         "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings to bytes")
     return ap.parse_args()
 
 
@@ -88,7 +98,12 @@ def main():
     bases = [synth.lowrank_basis(cfg, l, dev) for l in range(layers)]
 
     def gen(t):
-        return [synth.chunk_qkv(cfg, l, t, dev, basis=bases[l]) for l in range(layers)]
+        data = [synth.chunk_qkv(cfg, l, t, dev, basis=bases[l]) for l in range(layers)]
+        if args.zero_data:
+            for qkv in data:
+                for x in qkv:
+                    x.zero_()
+        return data
 
     # ---- untimed fill: chunk 0 with an empty cache
     tok0 = torch.arange(C, dtype=torch.int32, device=dev)
@@ -156,7 +171,7 @@ def main():
     elt = 2
     evict_bytes = Hkv * (M + C) * 4.0 + 2.0 * Hkv * B * d * elt * 2    # scores read + K,V rows read+written
     roof = {"kernel": "attn_fwd_bf16", "bound": "mfma", "achieved": fwd_flop / (fwd_ms * 1e-3) / 1e12,
-            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "traffic": None}
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "traffic": FWD_TRAFFIC_BYTES}
     roof["frac"] = roof["achieved"] / roof["peak"]
     kernels = {
         "attn_fwd_bf16": {"ms": fwd_ms, "tflops": roof["achieved"], "frac_mfma": roof["frac"]},
@@ -168,6 +183,14 @@ def main():
         "evict_call": {"ms": evict_ms, "gbs": evict_bytes / (evict_ms * 1e-3) / 1e9,
                        "frac_hbm": evict_bytes / (evict_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
     }
+
+    if args.copy_probe:
+        src = torch.ones((1 << 28,), dtype=torch.int32, device=dev)     # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- CPU baseline sample (oracle), before the gather buffers are allocated
     cpu = None
@@ -230,13 +253,13 @@ def main():
         "metric": "context tokens/sec through chunk-compress at 1M ctx; gather top-k latency (ms)",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "zeros (debug)" if args.zero_data else "synthetic",
         "config": {"workload": cfg.name + " steady-state chunk (cache full), all layers",
                    "layers": layers, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "chunk": C,
                    "budget": B, "obs_window": C, "gather": "cfg4_gather_1m: N=1048576 D=2048 nq=16 k=16384 r=8"},
         "gather_ms": None if gather is None else gather["ms"],
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "gather": gather,
-        "valid": layers == cfg.n_layers,
+        "valid": layers == cfg.n_layers and not args.zero_data,
     }
     print(json.dumps(line))
 
