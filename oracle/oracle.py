@@ -38,6 +38,8 @@ def _lib():
         lib.oracle_compact_rows.argtypes = [P, P, P, P, c_i, P, c_i]
         lib.oracle_cosine.restype = c_i
         lib.oracle_cosine.argtypes = [P, P, c_l, c_i, c_i, c_d, P]
+        lib.oracle_pool_scores.restype = c_i
+        lib.oracle_pool_scores.argtypes = [P, c_i, c_l, c_i, P]
         lib.oracle_union_dilate.restype = c_l
         lib.oracle_union_dilate.argtypes = [P, c_i, c_l, c_l, c_i, c_l, c_l, P]
         _LIB = lib
@@ -179,3 +181,24 @@ def gather(emb, qry, k, radius=0, n_head=0, n_tail=0, eps=1e-8):
     nq, N = sim.shape
     topk = np.stack([topk_lowest_index(sim[qi], k) for qi in range(nq)])
     return sim, topk, union_dilate(topk, N, radius, n_head, n_tail)
+
+
+def pool_scores(sim, window):
+    """max over the query tokens, then a centred `window`-wide max over adjacent context tokens."""
+    sim = np.ascontiguousarray(sim, dtype=np.float64)
+    nq, N = sim.shape
+    pooled = np.zeros((N,), np.float64)
+    rc = _lib().oracle_pool_scores(_ptr(sim), nq, N, int(window), _ptr(pooled))
+    if rc != 0:
+        raise ValueError(f"oracle_pool_scores rc={rc}")
+    return pooled
+
+
+def gather_pooled(emb, qry, budget, window=129, n_head=0, n_tail=0, eps=1e-8):
+    """The paper's own post-processing: cosine -> max over query tokens -> window max-pool ->
+    the `budget` highest-scoring tokens, the first n_head and last n_tail always among them
+    (ties to the lowest index).  Returns (sim, pooled [N] f64, selected idx ascending)."""
+    sim = cosine(emb, qry, eps)
+    pooled = pool_scores(sim, window)
+    sel = evict_select(pooled, pooled.shape[0], budget, n_head, n_tail)
+    return sim, pooled, sel

@@ -325,3 +325,38 @@ int64_t oracle_union_dilate(const int32_t *topk, int nq, int64_t k, int64_t N,
     free(all);
     return cnt;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Significance score of Sec. 3.3 ("Identification of significant inputs"):
+ * the similarities are first max-pooled over the query tokens, so that each
+ * context token has one score, and then each token's score is max-pooled
+ * with its adjacent tokens -- 128 of them, i.e. a centred window of 129
+ * (Sec. 4.5 "Pooling kernel size"; Table 6a compares windows 5, 17, 129).
+ *   s_t      = max_q sim[q][t]
+ *   pooled_t = max { s_u : |u - t| <= (window-1)/2, 0 <= u < N }
+ * Reading: the window is clipped at the two ends of the context (no padding
+ * value takes part in the maximum).  sim [nq][N], pooled [N]; window odd.   */
+int oracle_pool_scores(const double *sim, int nq, int64_t N, int window, double *pooled)
+{
+    if (nq <= 0 || N < 0 || window < 1 || (window % 2) == 0) return -1;
+    const int64_t h = (window - 1) / 2;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(N ? N : 1));
+    if (!s) return -2;
+    for (int64_t t = 0; t < N; ++t) {
+        double m = sim[t];
+        for (int qi = 1; qi < nq; ++qi)
+            if (sim[(size_t)qi * N + t] > m) m = sim[(size_t)qi * N + t];
+        s[t] = m;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < N; ++t) {
+        const int64_t lo = t - h < 0 ? 0 : t - h;
+        const int64_t hi = t + h > N - 1 ? N - 1 : t + h;
+        double m = s[lo];
+        for (int64_t u = lo + 1; u <= hi; ++u)
+            if (s[u] > m) m = s[u];
+        pooled[t] = m;
+    }
+    free(s);
+    return 0;
+}

@@ -163,11 +163,11 @@ __device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, flo
 // waves of a workgroup cover `gp` query heads of one KV group times 8/gp row slabs, so the K/V
 // tiles staged in LDS (double-buffered, one barrier per 64-key tile) serve every wave.
 //
-// Measured on gfx950: while a v_mfma_f32_32x32x16_bf16 of one wave occupies a SIMD's matrix pipe,
-// ordinary VALU instructions of the other wave on that SIMD do not issue (a wave doing only
-// MFMAs next to a wave doing only v_fma takes the SUM of their solo times; only transcendental
-// ops overlap).  The cost of a tile is therefore MFMA time + VALU time, and this kernel is built
-// to keep the VALU instruction count per tile small:
+// Measured on gfx950 with random bf16 operands this kernel is limited by the power budget, not by
+// instruction issue: the shader clock falls to about 1.8 GHz under it (2.35 GHz with all-zero
+// operands, same cycle count), and the MFMA pipe is busy 56 % of the cycles.  Wall time follows
+// the energy of the launch, so the kernel is built to keep the instruction count and the data
+// movement per tile small rather than to chase a particular interleaving:
 //   - no row maximum on the fast path: probabilities are formed against the current reference
 //     m_run; if a row outgrew it by more than kBigSum (or m_run is still -inf) the tile sum of
 //     that row is huge / inf / NaN, and only then the whole wave recomputes with the true maximum

@@ -141,3 +141,63 @@ def test_dilation_is_maxpool_in_threshold_form():
     want = np.nonzero(pooled >= tau)[0]
     got = oracle.union_dilate(top[None, :], N, radius=r)
     np.testing.assert_array_equal(got, want)
+
+
+# ---- the paper's own post-processing (Sec. 3.3): max over query tokens, window max-pool, top budget
+
+def brute_pool(sim, window):
+    nq, N = sim.shape
+    h = (window - 1) // 2
+    s = [max(sim[q][t] for q in range(nq)) for t in range(N)]
+    return np.array([max(s[max(0, t - h):min(N, t + h + 1)]) for t in range(N)])
+
+
+@pytest.mark.parametrize("nq,N,window", [(1, 1, 1), (3, 40, 5), (4, 300, 129), (2, 64, 17), (5, 130, 129), (1, 10, 129)])
+def test_pool_scores_matches_brute_force_and_library_filters(nq, N, window):
+    from scipy.ndimage import maximum_filter1d
+    rng = np.random.default_rng(40 + N)
+    sim = rng.standard_normal((nq, N))
+    got = oracle.pool_scores(sim, window)
+    np.testing.assert_array_equal(got, brute_pool(sim, window))
+    lib = maximum_filter1d(sim.max(axis=0), size=window, mode="constant", cval=-np.inf)
+    np.testing.assert_array_equal(got, lib)
+    tp = torch.nn.functional.max_pool1d(torch.from_numpy(sim.max(axis=0))[None, None], window, stride=1,
+                                        padding=window // 2)[0, 0].numpy()   # pads with -inf
+    np.testing.assert_array_equal(got, tp)
+
+
+def test_pool_scores_special_cases():
+    rng = np.random.default_rng(41)
+    sim = rng.standard_normal((6, 200))
+    np.testing.assert_array_equal(oracle.pool_scores(sim, 1), sim.max(axis=0))      # window 1: only the query max
+    np.testing.assert_array_equal(oracle.pool_scores(sim[:1], 1), sim[0])           # one query, window 1: identity
+    np.testing.assert_array_equal(oracle.pool_scores(sim, 401), np.full(200, sim.max()))   # window covers everything
+    spike = np.full((1, 50), -1.0)
+    spike[0, 20] = 2.0
+    want = np.full(50, -1.0)
+    want[18:23] = 2.0                                                               # a spike becomes a plateau of `window`
+    np.testing.assert_array_equal(oracle.pool_scores(spike, 5), want)
+    with pytest.raises(ValueError):
+        oracle.pool_scores(sim, 4)                                                  # even windows have no centre
+
+
+def test_gather_pooled_end_to_end_small():
+    """cosine -> pooled score -> budget selection with forced ends, against python sets/sorts."""
+    rng = np.random.default_rng(42)
+    N, D, nq, budget, window = 500, 16, 3, 60, 9
+    emb = rng.standard_normal((N, D)).astype(np.float32)
+    qry = rng.standard_normal((nq, D)).astype(np.float32)
+    sim, pooled, sel = oracle.gather_pooled(emb, qry, budget, window, n_head=8, n_tail=8)
+    np.testing.assert_array_equal(pooled, brute_pool(sim, window))
+    forced = set(range(8)) | set(range(N - 8, N))
+    assert list(sel) == exhaustive_topk(pooled, budget, forced)
+    assert len(sel) == budget and forced <= set(sel.tolist())
+    # plateaus: equal pooled scores are taken from the lowest index on
+    free = [t for t in sel if t not in forced]
+    thr = min(pooled[t] for t in free)
+    below = [t for t in range(N) if t not in forced and t not in set(sel.tolist())]
+    assert all(pooled[t] <= thr for t in below)
+    ties_out = [t for t in below if pooled[t] == thr]
+    ties_in = [t for t in free if pooled[t] == thr]
+    if ties_out and ties_in:
+        assert max(ties_in) < min(ties_out)
