@@ -178,6 +178,42 @@ reform_status reform_gather_similarity(const reform_gather_desc *desc,
                                        const void *emb, const void *qry, float *sim,
                                        void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------- */
+/* reform_gather_pooled -- the selection of Sec. 3.3 in the paper's own order
+ *
+ *     sim_qt   = cosine similarity as in reform_gather_topk                (Sec. 3.3, App. C.6)
+ *     s_t      = max_q sim_qt                       (max-pool over the query tokens, Sec. 3.3)
+ *     pooled_t = max { s_u : |u - t| <= (pool_window-1)/2, 0 <= u < n_ctx }
+ *                (each token's score max-pooled with its adjacent tokens; the paper uses 128
+ *                 neighbours = a window of 129, Sec. 4.5; the window is clipped at both ends)
+ *     sel      = the `budget` tokens with the largest pooled_t, the first n_head_keep and the
+ *                last n_tail_keep tokens always among them and counted inside the budget
+ *                (Sec. 3.3 keeps the initial and final 256 tokens; Sec. 4 gives budgets of 8k and
+ *                 16k), ties to the lowest index, ascending
+ *
+ *     emb      [n_ctx][dim], qry [n_query][dim]: contiguous, dtype
+ *     sel_idx  [budget] int32 out
+ *     pooled   [n_ctx] fp32 out, may be NULL (then it lives in the workspace only)
+ * Supported: as reform_gather_topk; pool_window odd, 1 <= pool_window <= 1025;
+ * n_head_keep + n_tail_keep <= budget <= n_ctx.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  dtype;
+    int64_t  n_ctx;
+    int32_t  dim, n_query, budget;
+    int32_t  pool_window, n_head_keep, n_tail_keep;
+    float    eps;
+} reform_pooled_desc;
+
+size_t reform_gather_pooled_workspace(const reform_pooled_desc *desc);
+
+reform_status reform_gather_pooled(const reform_pooled_desc *desc,
+                                   const void *emb, const void *qry,
+                                   int32_t *sel_idx, float *pooled,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
 const char *reform_status_string(reform_status status);
 
 /* Library version, major*10000 + minor*100 + patch.                                            */

@@ -21,6 +21,7 @@ EXPORTED = [
     "reform_chunk_attend_score_workspace", "reform_chunk_attend_score",
     "reform_evict_topk_compact_workspace", "reform_evict_topk_compact",
     "reform_gather_topk_workspace", "reform_gather_topk", "reform_gather_similarity",
+    "reform_gather_pooled_workspace", "reform_gather_pooled",
     "reform_status_string", "reform_version",
 ]
 
@@ -59,6 +60,14 @@ class GatherDesc(ctypes.Structure):
                 ("n_tail_keep", ctypes.c_int32), ("eps", ctypes.c_float)]
 
 
+class PooledDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("n_ctx", ctypes.c_int64),
+                ("dim", ctypes.c_int32), ("n_query", ctypes.c_int32), ("budget", ctypes.c_int32),
+                ("pool_window", ctypes.c_int32), ("n_head_keep", ctypes.c_int32),
+                ("n_tail_keep", ctypes.c_int32), ("eps", ctypes.c_float)]
+
+
 def library_path():
     return _LIB_PATH
 
@@ -87,6 +96,10 @@ def load_library():
     lib.reform_gather_topk.argtypes = [ctypes.POINTER(GatherDesc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.reform_gather_similarity.restype = ctypes.c_int
     lib.reform_gather_similarity.argtypes = [ctypes.POINTER(GatherDesc), vp, vp, vp, vp]
+    lib.reform_gather_pooled_workspace.restype = sz
+    lib.reform_gather_pooled_workspace.argtypes = [ctypes.POINTER(PooledDesc)]
+    lib.reform_gather_pooled.restype = ctypes.c_int
+    lib.reform_gather_pooled.argtypes = [ctypes.POINTER(PooledDesc), vp, vp, vp, vp, vp, sz, vp]
     lib.reform_status_string.restype = ctypes.c_char_p
     lib.reform_status_string.argtypes = [ctypes.c_int]
     lib.reform_version.restype = ctypes.c_int32
@@ -232,6 +245,37 @@ def reform_gather_similarity(emb, qry, eps=1e-8, sim=None, stream=None):
     rc = lib.reform_gather_similarity(ctypes.byref(desc), _ptr(emb), _ptr(qry), _ptr(sim), _stream(stream))
     _check(rc, "reform_gather_similarity")
     return sim
+
+
+def pooled_desc(emb, qry, budget, pool_window=129, n_head_keep=0, n_tail_keep=0, eps=1e-8):
+    N, D = emb.shape
+    nq, D2 = qry.shape
+    assert D == D2 and emb.dtype == qry.dtype
+    return PooledDesc(ctypes.sizeof(PooledDesc), _dtype_code(emb), N, D, nq, int(budget),
+                      int(pool_window), int(n_head_keep), int(n_tail_keep), float(eps))
+
+
+def reform_gather_pooled(emb, qry, budget, pool_window=129, n_head_keep=0, n_tail_keep=0, eps=1e-8,
+                         sel_idx=None, pooled=None, workspace=None, stream=None):
+    """Returns (sel_idx [budget] i32 ascending, pooled [N] f32)."""
+    lib = load_library()
+    assert emb.is_contiguous() and qry.is_contiguous()
+    dev = emb.device
+    if sel_idx is None:
+        sel_idx = torch.empty((budget,), dtype=torch.int32, device=dev)
+    if pooled is None:
+        pooled = torch.empty((emb.shape[0],), dtype=torch.float32, device=dev)
+    desc = pooled_desc(emb, qry, budget, pool_window, n_head_keep, n_tail_keep, eps)
+    need = lib.reform_gather_pooled_workspace(ctypes.byref(desc))
+    ws = _workspace(need, dev, workspace)
+    rc = lib.reform_gather_pooled(ctypes.byref(desc), _ptr(emb), _ptr(qry), _ptr(sel_idx), _ptr(pooled),
+                                  _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
+    _check(rc, "reform_gather_pooled")
+    return sel_idx, pooled
+
+
+def pooled_workspace_bytes(desc):
+    return load_library().reform_gather_pooled_workspace(ctypes.byref(desc))
 
 
 def attend_workspace_bytes(desc):

@@ -64,6 +64,14 @@ struct EvictParams {
     int row_bytes;      // head_dim * sizeof(element), multiple of 16
 };
 
+struct PoolParams {
+    const float *sim;    // [nq][ld]
+    float *pooled;       // [N]
+    SelParams sel;       // budget selection over pooled (one row)
+    long N, ld;
+    int nq, window;      // window odd, <= the kernel's maximum
+};
+
 struct GatherParams {
     const void *emb, *qry;
     float *sim;          // [nq][N]

@@ -17,6 +17,8 @@ hipError_t evict_fill_identity(int32_t *kept, int Hkv, int B, int n, hipStream_t
 
 hipError_t gather_similarity(GatherParams p, int dtype_is_bf16, hipStream_t st);
 hipError_t gather_select_union(GatherParams p, hipStream_t st);
+hipError_t gather_pool_select(const PoolParams &p, hipStream_t st);
+int gather_pool_max_window();
 }  // namespace reform
 
 using namespace reform;
@@ -106,6 +108,50 @@ GatherLayout gather_layout(const reform_gather_desc *d)
     L.blk = off;    off += align_up((size_t)d->n_query * L.nblk * 2 * sizeof(int));
     L.bitmap = off; off += align_up((size_t)L.nwords * sizeof(uint32_t));
     L.words = off;  off += align_up((size_t)L.nublk * sizeof(int));
+    L.total = off;
+    return L;
+}
+
+reform_gather_desc pooled_as_gather(const reform_pooled_desc *d)
+{
+    reform_gather_desc g;
+    std::memset(&g, 0, sizeof(g));
+    g.struct_size = sizeof(g);
+    g.dtype = d->dtype; g.n_ctx = d->n_ctx; g.dim = d->dim; g.n_query = d->n_query;
+    g.k = d->budget; g.eps = d->eps;
+    return g;
+}
+
+reform_status check_pooled(const reform_pooled_desc *d)
+{
+    if (!d || d->struct_size != sizeof(reform_pooled_desc)) return REFORM_ERR_INVALID_ARG;
+    const reform_gather_desc g = pooled_as_gather(d);
+    const reform_status rc = check_gather(&g);
+    if (rc != REFORM_OK) return rc;
+    if (d->pool_window < 1 || (d->pool_window % 2) == 0) return REFORM_ERR_INVALID_ARG;
+    if (d->n_head_keep < 0 || d->n_tail_keep < 0 ||
+        (int64_t)d->n_head_keep + d->n_tail_keep > d->budget)
+        return REFORM_ERR_INVALID_ARG;
+    if (d->pool_window > gather_pool_max_window()) return REFORM_ERR_UNSUPPORTED;
+    return REFORM_OK;
+}
+
+struct PooledLayout {
+    size_t sim, pooled, hist, prefix, krem, blk, total;
+    int nblk;
+};
+
+PooledLayout pooled_layout(const reform_pooled_desc *d)
+{
+    PooledLayout L;
+    L.nblk = (int)((d->n_ctx + 4095) / 4096);
+    size_t off = 0;
+    L.sim = off;    off += align_up((size_t)d->n_query * d->n_ctx * sizeof(float));
+    L.pooled = off; off += align_up((size_t)d->n_ctx * sizeof(float));
+    L.hist = off;   off += align_up((size_t)3 * 2048 * sizeof(int));
+    L.prefix = off; off += align_up((size_t)3 * sizeof(uint32_t));
+    L.krem = off;   off += align_up((size_t)3 * sizeof(int));
+    L.blk = off;    off += align_up((size_t)L.nblk * 2 * sizeof(int));
     L.total = off;
     return L;
 }
@@ -318,6 +364,47 @@ reform_status reform_gather_topk(const reform_gather_desc *d, const void *emb, c
     hipStream_t st = (hipStream_t)hip_stream;
     if (gather_similarity(p, d->dtype == REFORM_BF16, st) != hipSuccess) return REFORM_ERR_RUNTIME;
     return gather_select_union(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+size_t reform_gather_pooled_workspace(const reform_pooled_desc *d)
+{
+    if (check_pooled(d) != REFORM_OK) return 0;
+    return pooled_layout(d).total;
+}
+
+reform_status reform_gather_pooled(const reform_pooled_desc *d, const void *emb, const void *qry,
+                                   int32_t *sel_idx, float *pooled, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream)
+{
+    reform_status rc = check_pooled(d);
+    if (rc != REFORM_OK) return rc;
+    if (!emb || !qry || !sel_idx || !aligned16(emb) || !aligned16(qry)) return REFORM_ERR_INVALID_ARG;
+    const PooledLayout L = pooled_layout(d);
+    if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & (kAlign - 1)))
+        return REFORM_ERR_WORKSPACE;
+    char *ws = (char *)workspace;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const reform_gather_desc g = pooled_as_gather(d);
+    GatherParams gp;
+    fill_gather(gp, &g, emb, qry);
+    gp.sim = (float *)(ws + L.sim);
+    if (gather_similarity(gp, d->dtype == REFORM_BF16, st) != hipSuccess) return REFORM_ERR_RUNTIME;
+    PoolParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.sim = gp.sim;
+    p.pooled = pooled ? pooled : (float *)(ws + L.pooled);
+    p.N = d->n_ctx; p.ld = d->n_ctx; p.nq = d->n_query; p.window = d->pool_window;
+    p.sel.vals = p.pooled; p.sel.ld = d->n_ctx; p.sel.N = d->n_ctx;
+    p.sel.nq = 1; p.sel.k = d->budget;
+    p.sel.n_sink = d->n_head_keep; p.sel.n_recent = d->n_tail_keep;
+    p.sel.hist = (int *)(ws + L.hist);
+    p.sel.sel_prefix = (uint32_t *)(ws + L.prefix);
+    p.sel.sel_krem = (int *)(ws + L.krem);
+    p.sel.blk_cnt = (int *)(ws + L.blk);
+    p.sel.nblk = L.nblk;
+    p.sel.out_idx = sel_idx; p.sel.out_val = nullptr; p.sel.out_ld = d->budget;
+    return gather_pool_select(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 
 }  // extern "C"

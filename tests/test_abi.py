@@ -103,3 +103,28 @@ def test_gather_rejects_bad_arguments():
     assert call(mk()) == 3                                # no workspace
     assert lib.reform_gather_topk_workspace(ctypes.byref(mk())) >= 2 * 4096 * 4
     assert lib.reform_gather_similarity(ctypes.byref(mk()), fake, fake, None, None) == 1
+
+
+def test_gather_pooled_rejects_bad_arguments():
+    lib = binding.load_library()
+    mk = lambda **kw: binding.PooledDesc(**{**dict(struct_size=ctypes.sizeof(binding.PooledDesc),
+                                                   dtype=1, n_ctx=4096, dim=256, n_query=2, budget=600,
+                                                   pool_window=129, n_head_keep=256, n_tail_keep=256,
+                                                   eps=1e-8), **kw})
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda d, ws=None, nb=0: lib.reform_gather_pooled(ctypes.byref(d), fake, fake, fake, None,
+                                                             ws, nb, None)
+    assert call(mk(struct_size=8)) == 1
+    assert call(mk(budget=0)) == 1
+    assert call(mk(budget=5000)) == 1
+    assert call(mk(pool_window=128)) == 1                 # even: no centre
+    assert call(mk(pool_window=0)) == 1
+    assert call(mk(pool_window=1027)) == 2                # beyond the kernel's halo
+    assert call(mk(n_head_keep=400, n_tail_keep=256)) == 1   # forced tokens exceed the budget
+    assert call(mk(n_tail_keep=-1)) == 1
+    assert call(mk(dim=100)) == 2
+    assert call(mk()) == 3                                # no workspace
+    need = lib.reform_gather_pooled_workspace(ctypes.byref(mk()))
+    assert need >= 2 * 4096 * 4 + 4096 * 4                # similarity rows + pooled scores
+    assert call(mk(), ctypes.c_void_p(0x1100), need - 1) == 3
+    assert lib.reform_gather_pooled_workspace(ctypes.byref(mk(pool_window=2))) == 0
