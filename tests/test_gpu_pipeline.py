@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0):
+def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0, W=0, accumulate=False):
     Hq, Hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     cap, B = cfg.capacity, cfg.B
     rtol = RTOL[cfg.dtype]
@@ -28,6 +28,8 @@ def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0):
     pos = torch.full((Hkv, cap), -1, dtype=torch.int32, device=DEV)
     K_all = np.zeros((Hkv, cfg.L, d), np.float32)      # every token's original key / value
     V_all = np.zeros((Hkv, cfg.L, d), np.float32)
+    score = torch.zeros((Hkv, cap), dtype=torch.float32, device=DEV)
+    acc_ref = np.zeros((Hkv, cfg.L), np.float64)       # accumulate mode: the oracle's own running score per token
     M, subs_total, stats = 0, 0, []
     for t in range(cfg.n_chunks):
         q, k, v = synth.chunk_qkv(cfg, layer, t, plan=plan)
@@ -41,7 +43,11 @@ def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0):
         pos[:, M:n] = torch.arange(base, base + Ct, dtype=torch.int32, device=DEV)
         pos_before = pos.cpu().numpy()
         print(f"[pipeline] {cfg.name} chunk {t}/{cfg.n_chunks} M={M} Ct={Ct}", flush=True)
-        out, lse, score = binding.reform_chunk_attend_score(q.to(DEV), Kd, Vd, M, cfg.scale)
+        Wt = min(W, Ct)                                 # a ragged last chunk can be shorter than the window
+        if accumulate:
+            score[:, M:n] = 0                           # the new tokens start from zero
+        out, lse, _ = binding.reform_chunk_attend_score(q.to(DEV), Kd, Vd, M, cfg.scale, obs_window=Wt,
+                                                        accumulate=accumulate, score=score)
         kept = torch.full((Hkv, B), -1, dtype=torch.int32, device=DEV)
         score_gpu = score.cpu().numpy()
         new_len = binding.reform_evict_topk_compact(Kd, Vd, score, n, B, n_sink, n_recent, pos=pos,
@@ -72,7 +78,16 @@ def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0):
             for g in range(Hkv):
                 Ko[g, :n] = K_all[g, pos_before[g, :n]]
                 Vo[g, :n] = V_all[g, pos_before[g, :n]]
-            o_ref, l_ref, s_ref = oracle.attend_score(to_np(q), Ko, Vo, M, cfg.scale)
+            prev = None
+            if accumulate:
+                prev = np.zeros((Hkv, cap))
+                for g in range(Hkv):
+                    prev[g, :M] = acc_ref[g, pos_before[g, :M]]
+            o_ref, l_ref, s_ref = oracle.attend_score(to_np(q), Ko, Vo, M, cfg.scale, W=Wt,
+                                                      accumulate=accumulate, score_in=prev)
+            if accumulate:
+                for g in range(Hkv):
+                    acc_ref[g, pos_before[g, :n]] = s_ref[g, :n]
             assert_close(to_np(out), o_ref, rtol, f"out chunk {t}")
             assert_close(to_np(lse), l_ref, rtol, f"lse chunk {t}")
             assert_close(score_gpu[:, :n], s_ref[:, :n], rtol, f"score chunk {t}")
@@ -115,3 +130,41 @@ def test_workload5_scaled_adversarial_ragged_ties():
     needles = set(plan["needle_pos"].tolist())
     survived = np.mean([len(needles & set(final[g].tolist())) for g in range(cfg.n_kv_heads)])
     print(f"[pipeline] workload 5 (scaled): {survived:.1f} of 64 needles in the final cache", flush=True)
+
+
+def test_paper_mode_window_128_protected_256_256():
+    """The compression as the paper's experiments configure it (Sec. 4, common setup): only the
+    last 128 queries of a chunk observe, the first and the most recent 256 tokens always stay."""
+    cfg = synth.scaled(synth.STREAMS[2], L=4 * 1024 + 300, C=1024, B=1024)
+    stats, _, _ = lockstep(cfg, n_sink=256, n_recent=256, W=128)
+    for t, s in enumerate(stats[1:], start=1):
+        assert (s[:, :256] == np.arange(256)).all()
+        last = min((t + 1) * 1024, cfg.L)
+        assert (s[:, -256:] == np.arange(last - 256, last)).all()
+
+
+def test_accumulated_scores_across_chunks():
+    """accumulate = 1: a token's score is the attention mass it received over every chunk since
+    it entered the cache (the score row is compacted together with K and V)."""
+    cfg = synth.scaled(synth.STREAMS[2], L=5 * 512, C=512, B=768)
+    lockstep(cfg, W=128, accumulate=True)
+
+
+def test_tova_rule_last_query_only():
+    """TOVA as a drop-in compressor (Sec. 4.5, Table 6a): the keys are ranked by the attention of
+    the chunk's last query alone, i.e. obs_window = 1 (summing instead of averaging over the heads
+    of a group does not change the ranking)."""
+    cfg = synth.scaled(synth.STREAMS[5], L=4 * 1024 + 17, C=1024, B=384)
+    lockstep(cfg, W=1)
+
+
+def test_streaming_llm_rule_sinks_and_recents_fill_the_budget():
+    """StreamingLLM as a drop-in compressor (Sec. 4.5, Table 6a): n_sink + n_recent = B, so the
+    scores decide nothing and the cache is the first n_sink tokens plus the latest ones."""
+    cfg = synth.scaled(synth.STREAMS[2], L=4 * 640, C=640, B=640)
+    stats, subs, _ = lockstep(cfg, n_sink=4, n_recent=636, check_chunks=(3,))
+    assert subs == 0
+    for t, s in enumerate(stats):
+        last = (t + 1) * 640
+        want = np.concatenate([np.arange(4), np.arange(last - 636, last)]) if t else np.arange(640)
+        assert (s == want[None, :]).all()

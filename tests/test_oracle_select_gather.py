@@ -201,3 +201,11 @@ def test_gather_pooled_end_to_end_small():
     ties_in = [t for t in free if pooled[t] == thr]
     if ties_out and ties_in:
         assert max(ties_in) < min(ties_out)
+
+
+def test_forced_slots_filling_the_budget_ignore_the_scores():
+    """n_sink + n_recent = B is the StreamingLLM rule: first and latest tokens, whatever the scores."""
+    rng = np.random.default_rng(50)
+    s = rng.standard_normal(100)
+    kept = oracle.evict_select(s, 100, 20, n_sink=4, n_recent=16)
+    assert list(kept) == list(range(4)) + list(range(84, 100))
