@@ -40,6 +40,8 @@ def _lib():
         lib.oracle_cosine.argtypes = [P, P, c_l, c_i, c_i, c_d, P]
         lib.oracle_pool_scores.restype = c_i
         lib.oracle_pool_scores.argtypes = [P, c_i, c_l, c_i, P]
+        lib.oracle_embed_segment.restype = c_i
+        lib.oracle_embed_segment.argtypes = [P, c_l, c_i, c_l, P, c_l, c_l, c_d]
         lib.oracle_union_dilate.restype = c_l
         lib.oracle_union_dilate.argtypes = [P, c_i, c_l, c_l, c_i, c_l, c_l, P]
         _LIB = lib
@@ -202,3 +204,16 @@ def gather_pooled(emb, qry, budget, window=129, n_head=0, n_tail=0, eps=1e-8):
     pooled = pool_scores(sim, window)
     sel = evict_select(pooled, pooled.shape[0], budget, n_head, n_tail)
     return sim, pooled, sel
+
+
+def embed_segment(src, emb, col, eps=1e-12):
+    """src [n_rows, d] float32 (any row stride); emb [n_rows, D] float64, written in place at
+    columns [col, col+d): the L2-normalised rows of src."""
+    src = np.asarray(src, dtype=np.float32)
+    assert src.ndim == 2 and src.strides[1] == 4 and src.strides[0] % 4 == 0
+    assert emb.dtype == np.float64 and emb.flags.c_contiguous and emb.shape[0] == src.shape[0]
+    rc = _lib().oracle_embed_segment(_ptr(src), src.shape[0], src.shape[1], src.strides[0] // 4,
+                                     _ptr(emb), emb.shape[1], int(col), float(eps))
+    if rc != 0:
+        raise ValueError(f"oracle_embed_segment rc={rc}")
+    return emb

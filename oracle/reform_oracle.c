@@ -360,3 +360,29 @@ int oracle_pool_scores(const double *sim, int nq, int64_t N, int window, double 
     free(s);
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* One segment of the cross-layer context embedding (Sec. 3.2 "Combining
+ * multiple heads": e_comb = concat{ e_i / ||e_i|| : i in selected heads };
+ * Alg. 1 `emb.SaveSelected(qkv)`): the selected head's state of every token
+ * of the chunk, L2-normalised, written into columns [col, col+d) of the
+ * tokens' embedding rows.
+ * Reading: a zero vector has no direction; the norm is clamped from below by
+ * eps, so it stays zero instead of producing NaN.
+ * src: n_rows vectors of d floats, src_stride floats apart;
+ * emb: rows of emb_stride doubles; the segment of row r is emb[r*emb_stride+col ..].  */
+int oracle_embed_segment(const float *src, int64_t n_rows, int d, int64_t src_stride,
+                         double *emb, int64_t emb_stride, int64_t col, double eps)
+{
+    if (n_rows < 0 || d <= 0 || col < 0 || col + d > emb_stride || !(eps > 0.0)) return -1;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const float *x = src + (size_t)r * src_stride;
+        double ss = 0.0;
+        for (int c = 0; c < d; ++c) ss += (double)x[c] * (double)x[c];
+        double nrm = sqrt(ss);
+        if (nrm < eps) nrm = eps;
+        double *e = emb + (size_t)r * emb_stride + col;
+        for (int c = 0; c < d; ++c) e[c] = (double)x[c] / nrm;
+    }
+    return 0;
+}

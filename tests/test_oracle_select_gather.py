@@ -209,3 +209,54 @@ def test_forced_slots_filling_the_budget_ignore_the_scores():
     s = rng.standard_normal(100)
     kept = oracle.evict_select(s, 100, 20, n_sink=4, n_recent=16)
     assert list(kept) == list(range(4)) + list(range(84, 100))
+
+
+# ---- embedding construction (Sec. 3.2 "Combining multiple heads", Alg. 1 SaveSelected)
+
+def test_embed_segment_unit_norm_placement_and_strides():
+    rng = np.random.default_rng(60)
+    n, d, D = 37, 16, 64
+    big = rng.standard_normal((n, 3 * d)).astype(np.float32)       # the head sits inside a wider row
+    src = big[:, d:2 * d]
+    emb = np.full((n, D), 7.0)
+    oracle.embed_segment(src, emb, col=32)
+    want = src.astype(np.float64) / np.linalg.norm(src.astype(np.float64), axis=1, keepdims=True)
+    np.testing.assert_allclose(emb[:, 32:48], want, rtol=1e-14)
+    np.testing.assert_allclose(np.linalg.norm(emb[:, 32:48], axis=1), 1.0, rtol=1e-14)
+    assert np.all(emb[:, :32] == 7.0) and np.all(emb[:, 48:] == 7.0)      # other segments untouched
+    tn = torch.nn.functional.normalize(torch.from_numpy(src).double(), dim=1).numpy()
+    np.testing.assert_allclose(emb[:, 32:48], tn, rtol=1e-14)
+
+
+def test_embed_segment_scale_invariance_idempotence_and_zero_rows():
+    rng = np.random.default_rng(61)
+    src = rng.standard_normal((9, 8)).astype(np.float32)
+    a = oracle.embed_segment(src, np.zeros((9, 8)), 0)
+    b = oracle.embed_segment(src * np.float32(4.0), np.zeros((9, 8)), 0)      # x4 is exact in fp32
+    np.testing.assert_allclose(a, b, rtol=1e-15)
+    src[3] = 0.0
+    z = oracle.embed_segment(src, np.ones((9, 8)), 0)
+    assert np.all(z[3] == 0.0) and np.all(np.isfinite(z))
+    with pytest.raises(ValueError):
+        oracle.embed_segment(src, np.zeros((9, 12)), 8)                       # segment would overrun the row
+
+
+def test_combined_embedding_cosine_is_mean_of_per_head_cosines_end_to_end():
+    """The sentence after the e_comb equation: a cosine search on the concatenation of the
+    normalised heads equals the average of the per-head cosine scores."""
+    rng = np.random.default_rng(62)
+    n, d, H = 50, 12, 4
+    ctx = rng.standard_normal((H, n, d)).astype(np.float32)
+    qry = rng.standard_normal((H, 2, d)).astype(np.float32)
+    E = np.zeros((n, H * d))
+    U = np.zeros((2, H * d))
+    for h in range(H):
+        oracle.embed_segment(ctx[h], E, h * d)
+        oracle.embed_segment(qry[h], U, h * d)
+    sim = oracle.cosine(E.astype(np.float32), U.astype(np.float32))
+    per_head = np.zeros((2, n))
+    for h in range(H):
+        a = ctx[h].astype(np.float64)
+        b = qry[h].astype(np.float64)
+        per_head += (b @ a.T) / (np.linalg.norm(b, axis=1)[:, None] * np.linalg.norm(a, axis=1)[None, :])
+    np.testing.assert_allclose(sim, per_head / H, rtol=2e-6, atol=2e-7)      # E, U pass through float32
