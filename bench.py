@@ -276,6 +276,18 @@ def main():
             torch.cuda.synchronize()
             if r >= 2:
                 pool_times.append(a.elapsed_time(b))
+        # embedding construction for one chunk: 16 selected heads x C tokens, normalised into the store
+        emb_times = []
+        for r in range(5):
+            a, b = ev(), ev()
+            a.record()
+            for seg in range(16):
+                binding.reform_embed_save_selected(out[seg], emb, 0, seg * d)
+            b.record()
+            torch.cuda.synchronize()
+            if r >= 2:
+                emb_times.append(a.elapsed_time(b))
+        emb_times.sort()
         pool_times.sort()
         times.sort()
         sim_times.sort()
@@ -288,6 +300,8 @@ def main():
                   "similarity_gbs": (float(N) * gcfg.D * 2 + gcfg.n_query * N * 4.0) / (s_ms * 1e-3) / 1e9,
                   "union_count": int(uc.item()),
                   "pooled_ms": pool_times[len(pool_times) // 2],
+                  "embed_chunk_ms": emb_times[len(emb_times) // 2],
+                  "embed_chunk_gbs": 16 * 2.0 * C * d * 2 / (emb_times[len(emb_times) // 2] * 1e-3) / 1e9,
                   "pooled_config": "max over 16 query tokens, window 129, forced 256+256, budget 16384"}
 
     line = {

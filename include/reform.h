@@ -214,6 +214,36 @@ reform_status reform_gather_pooled(const reform_pooled_desc *desc,
                                    void *workspace, size_t workspace_bytes,
                                    void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------- */
+/* reform_embed_save_selected -- Alg. 1 `emb.SaveSelected(qkv)`, one selected head
+ *
+ *     emb[t][col + c] = x_t[c] / max(||x_t||, eps),  c in [0, head_dim)       (Sec. 3.2, the
+ *     e_comb equation: the context embedding of a token is the concatenation of the
+ *     L2-normalised Q/K/V states of the selected heads; one call writes one such segment for
+ *     the n_rows tokens of a chunk)
+ *
+ *     src   the selected head's state of the chunk's first token; token t's vector starts
+ *           src_row_stride elements further on for each t (so a [heads][rows][d] or a
+ *           [rows][heads][d] tensor can be addressed in place); dtype
+ *     emb   embedding row of the chunk's first token in the [n_ctx][emb_dim] store
+ *           (emb_row_stride = emb_dim elements); dtype; only columns [emb_col, emb_col+head_dim)
+ *           of the n_rows rows are written
+ * Supported: head_dim * sizeof(dtype) a multiple of 16 and at most 1024 bytes; strides and
+ * emb_col multiples of 16 bytes; src and emb 16-byte aligned.  Sums in fp32.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  dtype;
+    int64_t  n_rows;
+    int32_t  head_dim;
+    int32_t  emb_col;
+    int64_t  src_row_stride, emb_row_stride; /* in elements                                    */
+    float    eps;                            /* > 0; 1e-12 in the tests                        */
+} reform_embed_desc;
+
+reform_status reform_embed_save_selected(const reform_embed_desc *desc,
+                                         const void *src, void *emb, void *hip_stream);
+
 const char *reform_status_string(reform_status status);
 
 /* Library version, major*10000 + minor*100 + patch.                                            */

@@ -21,7 +21,7 @@ EXPORTED = [
     "reform_chunk_attend_score_workspace", "reform_chunk_attend_score",
     "reform_evict_topk_compact_workspace", "reform_evict_topk_compact",
     "reform_gather_topk_workspace", "reform_gather_topk", "reform_gather_similarity",
-    "reform_gather_pooled_workspace", "reform_gather_pooled",
+    "reform_gather_pooled_workspace", "reform_gather_pooled", "reform_embed_save_selected",
     "reform_status_string", "reform_version",
 ]
 
@@ -68,6 +68,14 @@ class PooledDesc(ctypes.Structure):
                 ("n_tail_keep", ctypes.c_int32), ("eps", ctypes.c_float)]
 
 
+class EmbedDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("n_rows", ctypes.c_int64),
+                ("head_dim", ctypes.c_int32), ("emb_col", ctypes.c_int32),
+                ("src_row_stride", ctypes.c_int64), ("emb_row_stride", ctypes.c_int64),
+                ("eps", ctypes.c_float)]
+
+
 def library_path():
     return _LIB_PATH
 
@@ -100,6 +108,8 @@ def load_library():
     lib.reform_gather_pooled_workspace.argtypes = [ctypes.POINTER(PooledDesc)]
     lib.reform_gather_pooled.restype = ctypes.c_int
     lib.reform_gather_pooled.argtypes = [ctypes.POINTER(PooledDesc), vp, vp, vp, vp, vp, sz, vp]
+    lib.reform_embed_save_selected.restype = ctypes.c_int
+    lib.reform_embed_save_selected.argtypes = [ctypes.POINTER(EmbedDesc), vp, vp, vp]
     lib.reform_status_string.restype = ctypes.c_char_p
     lib.reform_status_string.argtypes = [ctypes.c_int]
     lib.reform_version.restype = ctypes.c_int32
@@ -245,6 +255,21 @@ def reform_gather_similarity(emb, qry, eps=1e-8, sim=None, stream=None):
     rc = lib.reform_gather_similarity(ctypes.byref(desc), _ptr(emb), _ptr(qry), _ptr(sim), _stream(stream))
     _check(rc, "reform_gather_similarity")
     return sim
+
+
+def reform_embed_save_selected(src, emb, row0, col, eps=1e-12, stream=None):
+    """src [n_rows, d] (a view of one head's Q, K or V states; any row stride); writes the
+    normalised rows into emb[row0 : row0 + n_rows, col : col + d]."""
+    lib = load_library()
+    n, d = src.shape
+    assert src.stride(1) == 1 and emb.is_contiguous() and emb.dtype == src.dtype
+    assert 0 <= row0 and row0 + n <= emb.shape[0]
+    desc = EmbedDesc(ctypes.sizeof(EmbedDesc), _dtype_code(src), n, d, int(col), src.stride(0),
+                     emb.shape[1], float(eps))
+    dst = emb[row0:] if n else emb
+    rc = lib.reform_embed_save_selected(ctypes.byref(desc), _ptr(src), _ptr(dst), _stream(stream))
+    _check(rc, "reform_embed_save_selected")
+    return emb
 
 
 def pooled_desc(emb, qry, budget, pool_window=129, n_head_keep=0, n_tail_keep=0, eps=1e-8):

@@ -64,6 +64,15 @@ struct EvictParams {
     int row_bytes;      // head_dim * sizeof(element), multiple of 16
 };
 
+struct EmbedParams {
+    const void *src;     // first token's head vector
+    void *emb;           // embedding row of the first token
+    long n_rows;
+    long src_stride_bytes, emb_stride_bytes, col_bytes;
+    int pieces, group;   // 16-byte pieces per head vector; lanes per row (power of two >= pieces, <= 64)
+    float eps;
+};
+
 struct PoolParams {
     const float *sim;    // [nq][ld]
     float *pooled;       // [N]

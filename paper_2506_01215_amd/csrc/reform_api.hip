@@ -19,6 +19,7 @@ hipError_t gather_similarity(GatherParams p, int dtype_is_bf16, hipStream_t st);
 hipError_t gather_select_union(GatherParams p, hipStream_t st);
 hipError_t gather_pool_select(const PoolParams &p, hipStream_t st);
 int gather_pool_max_window();
+hipError_t embed_save(const EmbedParams &p, bool bf16, hipStream_t st);
 }  // namespace reform
 
 using namespace reform;
@@ -405,6 +406,37 @@ reform_status reform_gather_pooled(const reform_pooled_desc *d, const void *emb,
     p.sel.nblk = L.nblk;
     p.sel.out_idx = sel_idx; p.sel.out_val = nullptr; p.sel.out_ld = d->budget;
     return gather_pool_select(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+reform_status reform_embed_save_selected(const reform_embed_desc *d, const void *src, void *emb,
+                                         void *hip_stream)
+{
+    if (!d || d->struct_size != sizeof(reform_embed_desc)) return REFORM_ERR_INVALID_ARG;
+    if (d->dtype != REFORM_F32 && d->dtype != REFORM_BF16) return REFORM_ERR_INVALID_ARG;
+    if (d->n_rows < 0 || d->head_dim <= 0 || d->emb_col < 0) return REFORM_ERR_INVALID_ARG;
+    if (d->src_row_stride < d->head_dim || d->emb_row_stride < (int64_t)d->emb_col + d->head_dim)
+        return REFORM_ERR_INVALID_ARG;
+    if (!(d->eps > 0.f) || !std::isfinite(d->eps)) return REFORM_ERR_INVALID_ARG;
+    if (!src || !emb) return REFORM_ERR_INVALID_ARG;
+    const size_t es = elt_size(d->dtype);
+    const size_t row_bytes = (size_t)d->head_dim * es;
+    if (row_bytes % 16 || row_bytes > 1024) return REFORM_ERR_UNSUPPORTED;
+    if (((size_t)d->src_row_stride * es) % 16 || ((size_t)d->emb_row_stride * es) % 16 ||
+        ((size_t)d->emb_col * es) % 16 || !aligned16(src) || !aligned16(emb))
+        return REFORM_ERR_UNSUPPORTED;
+    EmbedParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.src = src; p.emb = emb; p.n_rows = d->n_rows;
+    p.src_stride_bytes = (long)(d->src_row_stride * es);
+    p.emb_stride_bytes = (long)(d->emb_row_stride * es);
+    p.col_bytes = (long)(d->emb_col * es);
+    p.pieces = (int)(row_bytes / 16);
+    p.group = 1;
+    while (p.group < p.pieces) p.group *= 2;
+    p.eps = d->eps;
+    return embed_save(p, d->dtype == REFORM_BF16, (hipStream_t)hip_stream) == hipSuccess
+               ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 
 }  // extern "C"

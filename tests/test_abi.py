@@ -128,3 +128,24 @@ def test_gather_pooled_rejects_bad_arguments():
     assert need >= 2 * 4096 * 4 + 4096 * 4                # similarity rows + pooled scores
     assert call(mk(), ctypes.c_void_p(0x1100), need - 1) == 3
     assert lib.reform_gather_pooled_workspace(ctypes.byref(mk(pool_window=2))) == 0
+
+
+def test_embed_save_rejects_bad_arguments():
+    lib = binding.load_library()
+    mk = lambda **kw: binding.EmbedDesc(**{**dict(struct_size=ctypes.sizeof(binding.EmbedDesc), dtype=1,
+                                                  n_rows=100, head_dim=128, emb_col=256,
+                                                  src_row_stride=128, emb_row_stride=2048, eps=1e-12),
+                                           **kw})
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda d, s=fake, e=fake: lib.reform_embed_save_selected(ctypes.byref(d), s, e, None)
+    assert call(mk(struct_size=4)) == 1
+    assert call(mk(dtype=3)) == 1
+    assert call(mk(n_rows=-1)) == 1
+    assert call(mk(emb_col=2000)) == 1                    # the segment would overrun the row
+    assert call(mk(src_row_stride=64)) == 1               # rows overlap
+    assert call(mk(eps=0.0)) == 1
+    assert call(mk(), None) == 1
+    assert call(mk(head_dim=100, src_row_stride=100)) == 2     # 200-byte rows
+    assert call(mk(head_dim=1024, src_row_stride=1024, emb_col=0)) == 2   # 2 KB rows
+    assert call(mk(emb_col=4)) == 2                       # misaligned segment
+    assert call(mk(), ctypes.c_void_p(0x1008)) == 2       # misaligned source
