@@ -42,6 +42,8 @@ def _lib():
         lib.oracle_pool_scores.argtypes = [P, c_i, c_l, c_i, P]
         lib.oracle_embed_segment.restype = c_i
         lib.oracle_embed_segment.argtypes = [P, c_l, c_i, c_l, P, c_l, c_l, c_d]
+        lib.oracle_rerotate_keys.restype = c_i
+        lib.oracle_rerotate_keys.argtypes = [P, P, c_l, c_i, c_i, c_d, P]
         lib.oracle_union_dilate.restype = c_l
         lib.oracle_union_dilate.argtypes = [P, c_i, c_l, c_l, c_i, c_l, c_l, P]
         _LIB = lib
@@ -217,3 +219,18 @@ def embed_segment(src, emb, col, eps=1e-12):
     if rc != 0:
         raise ValueError(f"oracle_embed_segment rc={rc}")
     return emb
+
+
+def rerotate_keys(k, kept, theta=10000.0, rot=None):
+    """k [n_rows, d] float32: one head's compacted key rows; kept [n_rows]: the slot each row came
+    from.  Returns the rows rotated by (r - kept[r]) positions, float64."""
+    k = _f32(k)
+    kept = np.ascontiguousarray(kept, dtype=np.int32)
+    n, d = k.shape
+    assert kept.shape == (n,)
+    out = np.zeros((n, d), np.float64)
+    rc = _lib().oracle_rerotate_keys(_ptr(k), _ptr(kept), n, d, d if rot is None else int(rot),
+                                     float(theta), _ptr(out))
+    if rc != 0:
+        raise ValueError(f"oracle_rerotate_keys rc={rc}")
+    return out

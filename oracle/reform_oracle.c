@@ -386,3 +386,39 @@ int oracle_embed_segment(const float *src, int64_t n_rows, int d, int64_t src_st
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Position reassignment after compression (Sec. 3.1: after compression the
+ * tokens of the compressed cache get consecutive position ids).  For a cache
+ * that stores rotary-embedded keys this means: the key that sat at slot
+ * kept[r] (position id kept[r] under the numbering of the chunk just
+ * forwarded) now sits at slot r and must carry position id r, i.e. it is
+ * rotated by delta = r - kept[r] <= 0 positions.
+ * Reading (the paper names no rotary convention): the half-split pairing of
+ * the models it evaluates (Mistral, Qwen2.5): element c is paired with
+ * element c + rot/2, c in [0, rot/2), frequency theta^(-2c/rot); elements
+ * beyond `rot` are not rotated:
+ *     x'_c       = x_c cos(a) - x_{c+rot/2} sin(a)
+ *     x'_{c+rot/2} = x_{c+rot/2} cos(a) + x_c sin(a),   a = delta * theta^(-2c/rot)
+ * k: rows already compacted, [n_rows][d] floats of one head; kept [n_rows];
+ * out [n_rows][d] doubles.                                                   */
+int oracle_rerotate_keys(const float *k, const int32_t *kept, int64_t n_rows, int d, int rot,
+                         double theta, double *out)
+{
+    if (n_rows < 0 || d <= 0 || rot < 0 || rot > d || (rot % 2) || !(theta > 0.0)) return -1;
+    const int half = rot / 2;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const float *x = k + (size_t)r * d;
+        double *y = out + (size_t)r * d;
+        const double delta = (double)r - (double)kept[r];
+        for (int c = 0; c < d; ++c) y[c] = (double)x[c];
+        for (int c = 0; c < half; ++c) {
+            const double a = delta * pow(theta, -2.0 * (double)c / (double)rot);
+            const double cs = cos(a), sn = sin(a);
+            const double x0 = (double)x[c], x1 = (double)x[c + half];
+            y[c] = x0 * cs - x1 * sn;
+            y[c + half] = x1 * cs + x0 * sn;
+        }
+    }
+    return 0;
+}
