@@ -123,7 +123,7 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []                                 # (e0, e1, e2, e3) per timed layer-step
 
-    mode = {"obs_window": 0, "n_sink": 0, "n_recent": 0}      # the default workload: W = C, nothing forced
+    mode = {"obs_window": 0, "n_sink": 0, "n_recent": 0, "rope": False}   # default workload: W = C, nothing forced
 
     def step(s, timed):
         data = inputs[s % pool]
@@ -135,7 +135,7 @@ def main():
             Vc[l][:, M:M + C].copy_(v)         # written there by the QKV projection)
             pos[l][:, M:M + C] = tok
             if timed:
-                e = [ev() for _ in range(4)]
+                e = [ev() for _ in range(5)]
                 e[0].record()
                 binding.reform_chunk_attend_score(q, Kc[l], Vc[l], M, cfg.scale, obs_window=W, out=out,
                                                   lse=lse, score=score, workspace=ws_attn, phases=1)
@@ -146,12 +146,17 @@ def main():
                 binding.reform_evict_topk_compact(Kc[l], Vc[l], score, M + C, B, ns, nr, pos=pos[l],
                                                   kept_idx=kept, workspace=ws_evict)
                 e[3].record()
+                if mode["rope"]:
+                    binding.reform_rerotate_keys(Kc[l], kept, B, 1e6)
+                e[4].record()
                 marks.append(e)
             else:
                 binding.reform_chunk_attend_score(q, Kc[l], Vc[l], M, cfg.scale, obs_window=W, out=out,
                                                   lse=lse, score=score, workspace=ws_attn)
                 binding.reform_evict_topk_compact(Kc[l], Vc[l], score, M + C, B, ns, nr, pos=pos[l],
                                                   kept_idx=kept, workspace=ws_evict)
+                if mode["rope"]:
+                    binding.reform_rerotate_keys(Kc[l], kept, B, 1e6)
 
     for s in range(W_steps):
         step(s, False)
@@ -191,7 +196,7 @@ def main():
     # only the last 128 queries of a chunk observe, first and most recent 256 tokens always kept);
     # reported beside the headline figure, never instead of it
     n_main = len(marks)
-    mode.update(obs_window=128, n_sink=256, n_recent=256)
+    mode.update(obs_window=128, n_sink=256, n_recent=256, rope=True)
     step(W_steps + K_steps, False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -199,11 +204,13 @@ def main():
     torch.cuda.synchronize()
     wall_pm = time.perf_counter() - t1
     pm = marks[n_main:]
-    paper_mode = {"config": "obs_window 128, n_sink 256, n_recent 256", "tokens_per_s": C / wall_pm,
+    paper_mode = {"config": "obs_window 128, n_sink 256, n_recent 256, keys re-rotated to consecutive "
+                            "positions (theta 1e6)", "tokens_per_s": C / wall_pm,
                   "ms_per_step": wall_pm * 1e3,
                   "attn_fwd_ms": sum(e[0].elapsed_time(e[1]) for e in pm) / len(pm),
                   "attn_score_ms": sum(e[1].elapsed_time(e[2]) for e in pm) / len(pm),
-                  "evict_ms": sum(e[2].elapsed_time(e[3]) for e in pm) / len(pm)}
+                  "evict_ms": sum(e[2].elapsed_time(e[3]) for e in pm) / len(pm),
+                  "rerotate_ms": sum(e[3].elapsed_time(e[4]) for e in pm) / len(pm)}
     marks = marks[:n_main]
 
     if args.copy_probe:
@@ -287,6 +294,20 @@ def main():
             torch.cuda.synchronize()
             if r >= 2:
                 emb_times.append(a.elapsed_time(b))
+        # the selected tokens' input embeddings (hidden 4096, bf16) gathered for recomputation
+        table = torch.empty((N, 4096), dtype=torch.bfloat16, device=dev).normal_()
+        rows_out = torch.empty((16384, 4096), dtype=torch.bfloat16, device=dev)
+        rows_times = []
+        for r in range(5):
+            a, b = ev(), ev()
+            a.record()
+            binding.reform_gather_rows(table, psel, out=rows_out)
+            b.record()
+            torch.cuda.synchronize()
+            if r >= 2:
+                rows_times.append(a.elapsed_time(b))
+        rows_times.sort()
+        del table
         emb_times.sort()
         pool_times.sort()
         times.sort()
@@ -300,6 +321,8 @@ def main():
                   "similarity_gbs": (float(N) * gcfg.D * 2 + gcfg.n_query * N * 4.0) / (s_ms * 1e-3) / 1e9,
                   "union_count": int(uc.item()),
                   "pooled_ms": pool_times[len(pool_times) // 2],
+                  "rows_ms": rows_times[len(rows_times) // 2],
+                  "rows_gbs": 2.0 * 16384 * 8192 / (rows_times[len(rows_times) // 2] * 1e-3) / 1e9,
                   "embed_chunk_ms": emb_times[len(emb_times) // 2],
                   "embed_chunk_gbs": 16 * 2.0 * C * d * 2 / (emb_times[len(emb_times) // 2] * 1e-3) / 1e9,
                   "pooled_config": "max over 16 query tokens, window 129, forced 256+256, budget 16384"}

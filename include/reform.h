@@ -244,6 +244,61 @@ typedef struct {
 reform_status reform_embed_save_selected(const reform_embed_desc *desc,
                                          const void *src, void *emb, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------- */
+/* reform_rerotate_keys -- consecutive position ids after compression (Sec. 3.1)
+ *
+ * For a cache that stores rotary-embedded keys: after reform_evict_topk_compact the key at slot
+ * r came from slot kept_idx[r] and is rotated by delta = r - kept_idx[r] positions, in place:
+ *     a           = delta * theta^(-2c/rotary_dim),              c in [0, rotary_dim/2)
+ *     k'[c]       = k[c] cos a - k[c + rotary_dim/2] sin a
+ *     k'[c+rd/2]  = k[c + rotary_dim/2] cos a + k[c] sin a       (half-split pairing, as in the
+ *                                                               models the paper evaluates)
+ * Elements [rotary_dim, head_dim) and rows with delta = 0 are not touched; V is not rotated.
+ *
+ *     k         [n_kv_heads][capacity][head_dim], dtype, rows [0, n_rows) rotated in place
+ *     kept_idx  [n_kv_heads][budget] int32 as written by reform_evict_topk_compact
+ * Angles are formed in fp64 and reduced to a fraction of a turn before the fp32 sine/cosine.
+ * Supported: rotary_dim even, rotary_dim/2 * sizeof(dtype) a multiple of 16; 0 <= n_rows <=
+ * min(budget, capacity).
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  dtype;
+    int32_t  n_kv_heads, head_dim, capacity;
+    int32_t  n_rows, budget;
+    int32_t  rotary_dim;                     /* <= head_dim                                    */
+    float    theta;                          /* rotary base, > 1 (10000, 1e6, ...)             */
+} reform_rope_desc;
+
+reform_status reform_rerotate_keys(const reform_rope_desc *desc, void *k, const int32_t *kept_idx,
+                                   void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------- */
+/* reform_gather_rows -- the inputs that are recomputed (Sec. 3.3 "On-Demand Cache
+ * Recomputation"; Alg. 1: the selected tokens' input embeddings are gathered and forwarded again)
+ *
+ *     out[i] = table[idx[i]],   i in [0, n)   with n = n_idx, or min(*count, n_idx) if count != NULL
+ *
+ *     table  [n_table][row_bytes] bytes, any element type
+ *     idx    [n_idx] int32 (the union_idx of reform_gather_topk or the sel_idx of
+ *            reform_gather_pooled)
+ *     count  one int32 in device memory or NULL (the union_count of reform_gather_topk, so the
+ *            caller needs no host round trip)
+ *     out    [n_idx][row_bytes] bytes; rows >= n are not written
+ *     err    one int32 in device memory or NULL; bit 0 is set if an index was outside the
+ *            table (that row is then skipped, never read); the caller clears it
+ * Supported: row_bytes a multiple of 16, table and out 16-byte aligned.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  reserved;                       /* 0                                              */
+    int64_t  n_table, n_idx, row_bytes;
+} reform_rows_desc;
+
+reform_status reform_gather_rows(const reform_rows_desc *desc, const void *table,
+                                 const int32_t *idx, const int32_t *count, void *out,
+                                 int32_t *err, void *hip_stream);
+
 const char *reform_status_string(reform_status status);
 
 /* Library version, major*10000 + minor*100 + patch.                                            */

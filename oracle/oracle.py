@@ -44,6 +44,8 @@ def _lib():
         lib.oracle_embed_segment.argtypes = [P, c_l, c_i, c_l, P, c_l, c_l, c_d]
         lib.oracle_rerotate_keys.restype = c_i
         lib.oracle_rerotate_keys.argtypes = [P, P, c_l, c_i, c_i, c_d, P]
+        lib.oracle_gather_rows.restype = c_i
+        lib.oracle_gather_rows.argtypes = [P, c_l, c_l, P, c_l, P]
         lib.oracle_union_dilate.restype = c_l
         lib.oracle_union_dilate.argtypes = [P, c_i, c_l, c_l, c_i, c_l, c_l, P]
         _LIB = lib
@@ -233,4 +235,16 @@ def rerotate_keys(k, kept, theta=10000.0, rot=None):
                                      float(theta), _ptr(out))
     if rc != 0:
         raise ValueError(f"oracle_rerotate_keys rc={rc}")
+    return out
+
+
+def gather_rows(table, idx):
+    """table [n, ...] any dtype (C-contiguous); idx int32.  Returns table[idx] (raw byte copy)."""
+    table = np.ascontiguousarray(table)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    row_bytes = table[0].nbytes if table.shape[0] else int(np.prod(table.shape[1:])) * table.itemsize
+    out = np.zeros((idx.shape[0],) + table.shape[1:], table.dtype)
+    rc = _lib().oracle_gather_rows(_ptr(table), table.shape[0], row_bytes, _ptr(idx), idx.shape[0], _ptr(out))
+    if rc != 0:
+        raise ValueError(f"oracle_gather_rows rc={rc}")
     return out

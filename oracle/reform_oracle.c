@@ -422,3 +422,20 @@ int oracle_rerotate_keys(const float *k, const int32_t *kept, int64_t n_rows, in
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Gathering the inputs that are recomputed (Sec. 3.3 "On-Demand Cache
+ * Recomputation"; Alg. 1 `relevant_inputs <- GatherRelevant(input, emb)`):
+ * the rows of the input-embedding table named by the selected token indices,
+ * in the given (ascending) order.  table [n_table][row_bytes] raw bytes,
+ * out [n_idx][row_bytes].  Returns 0, or -1 on an index outside the table.   */
+int oracle_gather_rows(const unsigned char *table, int64_t n_table, int64_t row_bytes,
+                       const int32_t *idx, int64_t n_idx, unsigned char *out)
+{
+    if (n_table < 0 || row_bytes <= 0 || n_idx < 0) return -1;
+    for (int64_t i = 0; i < n_idx; ++i) {
+        if (idx[i] < 0 || idx[i] >= n_table) return -1;
+        memcpy(out + (size_t)i * row_bytes, table + (size_t)idx[i] * row_bytes, (size_t)row_bytes);
+    }
+    return 0;
+}

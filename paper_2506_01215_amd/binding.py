@@ -22,6 +22,7 @@ EXPORTED = [
     "reform_evict_topk_compact_workspace", "reform_evict_topk_compact",
     "reform_gather_topk_workspace", "reform_gather_topk", "reform_gather_similarity",
     "reform_gather_pooled_workspace", "reform_gather_pooled", "reform_embed_save_selected",
+    "reform_rerotate_keys", "reform_gather_rows",
     "reform_status_string", "reform_version",
 ]
 
@@ -76,6 +77,18 @@ class EmbedDesc(ctypes.Structure):
                 ("eps", ctypes.c_float)]
 
 
+class RowsDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("reserved", ctypes.c_int32),
+                ("n_table", ctypes.c_int64), ("n_idx", ctypes.c_int64), ("row_bytes", ctypes.c_int64)]
+
+
+class RopeDesc(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("capacity", ctypes.c_int32), ("n_rows", ctypes.c_int32), ("budget", ctypes.c_int32),
+                ("rotary_dim", ctypes.c_int32), ("theta", ctypes.c_float)]
+
+
 def library_path():
     return _LIB_PATH
 
@@ -110,6 +123,10 @@ def load_library():
     lib.reform_gather_pooled.argtypes = [ctypes.POINTER(PooledDesc), vp, vp, vp, vp, vp, sz, vp]
     lib.reform_embed_save_selected.restype = ctypes.c_int
     lib.reform_embed_save_selected.argtypes = [ctypes.POINTER(EmbedDesc), vp, vp, vp]
+    lib.reform_rerotate_keys.restype = ctypes.c_int
+    lib.reform_rerotate_keys.argtypes = [ctypes.POINTER(RopeDesc), vp, vp, vp]
+    lib.reform_gather_rows.restype = ctypes.c_int
+    lib.reform_gather_rows.argtypes = [ctypes.POINTER(RowsDesc), vp, vp, vp, vp, vp, vp]
     lib.reform_status_string.restype = ctypes.c_char_p
     lib.reform_status_string.argtypes = [ctypes.c_int]
     lib.reform_version.restype = ctypes.c_int32
@@ -270,6 +287,34 @@ def reform_embed_save_selected(src, emb, row0, col, eps=1e-12, stream=None):
     rc = lib.reform_embed_save_selected(ctypes.byref(desc), _ptr(src), _ptr(dst), _stream(stream))
     _check(rc, "reform_embed_save_selected")
     return emb
+
+
+def reform_rerotate_keys(k, kept_idx, n_rows, theta=10000.0, rotary_dim=None, stream=None):
+    """Rotates the compacted key rows [0, n_rows) of every head in place by (r - kept_idx[r]) positions."""
+    lib = load_library()
+    assert k.is_contiguous() and kept_idx.is_contiguous() and kept_idx.dtype == torch.int32
+    Hkv, cap, d = k.shape
+    assert kept_idx.shape[0] == Hkv
+    desc = RopeDesc(ctypes.sizeof(RopeDesc), _dtype_code(k), Hkv, d, cap, int(n_rows), kept_idx.shape[1],
+                    d if rotary_dim is None else int(rotary_dim), float(theta))
+    rc = lib.reform_rerotate_keys(ctypes.byref(desc), _ptr(k), _ptr(kept_idx), _stream(stream))
+    _check(rc, "reform_rerotate_keys")
+    return k
+
+
+def reform_gather_rows(table, idx, count=None, out=None, err=None, stream=None):
+    """out[i] = table[idx[i]]; `count` (device int32 scalar) limits the rows taken."""
+    lib = load_library()
+    assert table.is_contiguous() and idx.is_contiguous() and idx.dtype == torch.int32 and idx.dim() == 1
+    row_bytes = table[0].numel() * table.element_size()
+    if out is None:
+        out = torch.empty((idx.shape[0],) + tuple(table.shape[1:]), dtype=table.dtype, device=table.device)
+    assert out.is_contiguous() and out.shape[0] >= idx.shape[0]
+    desc = RowsDesc(ctypes.sizeof(RowsDesc), 0, table.shape[0], idx.shape[0], row_bytes)
+    rc = lib.reform_gather_rows(ctypes.byref(desc), _ptr(table), _ptr(idx), _ptr(count), _ptr(out),
+                                _ptr(err), _stream(stream))
+    _check(rc, "reform_gather_rows")
+    return out
 
 
 def pooled_desc(emb, qry, budget, pool_window=129, n_head_keep=0, n_tail_keep=0, eps=1e-8):

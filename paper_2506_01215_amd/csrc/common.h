@@ -64,6 +64,24 @@ struct EvictParams {
     int row_bytes;      // head_dim * sizeof(element), multiple of 16
 };
 
+struct RowsParams {
+    const void *table;       // [n_table][row_bytes]
+    void *out;               // [n_idx][row_bytes]
+    const int32_t *idx;      // [n_idx]
+    const int32_t *count;    // nullable device scalar: only the first min(*count, n_idx) indices are used
+    int *err;                // nullable device word, bit 0 set if an index was outside the table
+    long n_table, n_idx, row_bytes, pieces;
+};
+
+struct RopeParams {
+    void *k;                 // [Hkv][cap][d], rows [0, n_rows) already compacted
+    const int32_t *kept;     // [Hkv][kept_ld]: slot each row came from
+    long n_rows, cap, kept_ld;
+    int Hkv, rot;            // rot: rotated leading elements of a row (even)
+    int row_bytes;
+    double neg2_log2_theta_over_rot;   // -2 log2(theta) / rot
+};
+
 struct EmbedParams {
     const void *src;     // first token's head vector
     void *emb;           // embedding row of the first token

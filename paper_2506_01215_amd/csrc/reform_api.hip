@@ -20,6 +20,8 @@ hipError_t gather_select_union(GatherParams p, hipStream_t st);
 hipError_t gather_pool_select(const PoolParams &p, hipStream_t st);
 int gather_pool_max_window();
 hipError_t embed_save(const EmbedParams &p, bool bf16, hipStream_t st);
+hipError_t rope_rerotate_launch(const RopeParams &p, bool bf16, hipStream_t st);
+hipError_t gather_rows_launch(const RowsParams &p, hipStream_t st);
 }  // namespace reform
 
 using namespace reform;
@@ -437,6 +439,49 @@ reform_status reform_embed_save_selected(const reform_embed_desc *d, const void 
     p.eps = d->eps;
     return embed_save(p, d->dtype == REFORM_BF16, (hipStream_t)hip_stream) == hipSuccess
                ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+reform_status reform_rerotate_keys(const reform_rope_desc *d, void *k, const int32_t *kept_idx,
+                                   void *hip_stream)
+{
+    if (!d || d->struct_size != sizeof(reform_rope_desc)) return REFORM_ERR_INVALID_ARG;
+    if (d->dtype != REFORM_F32 && d->dtype != REFORM_BF16) return REFORM_ERR_INVALID_ARG;
+    if (d->n_kv_heads <= 0 || d->head_dim <= 0 || d->capacity <= 0 || d->budget <= 0)
+        return REFORM_ERR_INVALID_ARG;
+    if (d->n_rows < 0 || d->n_rows > d->budget || d->n_rows > d->capacity) return REFORM_ERR_INVALID_ARG;
+    if (d->rotary_dim < 0 || d->rotary_dim > d->head_dim || (d->rotary_dim % 2)) return REFORM_ERR_INVALID_ARG;
+    if (!(d->theta > 1.f) || !std::isfinite(d->theta)) return REFORM_ERR_INVALID_ARG;
+    if (!k || !kept_idx) return REFORM_ERR_INVALID_ARG;
+    const size_t es = elt_size(d->dtype);
+    if (((size_t)d->rotary_dim / 2 * es) % 16 || ((size_t)d->head_dim * es) % 16 || !aligned16(k))
+        return REFORM_ERR_UNSUPPORTED;
+    if (d->n_kv_heads > 65535) return REFORM_ERR_UNSUPPORTED;
+    RopeParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.k = k; p.kept = kept_idx;
+    p.n_rows = d->n_rows; p.cap = d->capacity; p.kept_ld = d->budget;
+    p.Hkv = d->n_kv_heads; p.rot = d->rotary_dim;
+    p.row_bytes = (int)(d->head_dim * es);
+    p.neg2_log2_theta_over_rot = d->rotary_dim ? -2.0 * std::log2((double)d->theta) / d->rotary_dim : 0.0;
+    return rope_rerotate_launch(p, d->dtype == REFORM_BF16, (hipStream_t)hip_stream) == hipSuccess
+               ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+reform_status reform_gather_rows(const reform_rows_desc *d, const void *table, const int32_t *idx,
+                                 const int32_t *count, void *out, int32_t *err, void *hip_stream)
+{
+    if (!d || d->struct_size != sizeof(reform_rows_desc) || d->reserved != 0) return REFORM_ERR_INVALID_ARG;
+    if (d->n_table <= 0 || d->n_idx < 0 || d->row_bytes <= 0) return REFORM_ERR_INVALID_ARG;
+    if (!table || !out || (!idx && d->n_idx > 0)) return REFORM_ERR_INVALID_ARG;
+    if (d->n_table >= (1ll << 31) || d->n_idx >= (1ll << 31)) return REFORM_ERR_UNSUPPORTED;
+    if (d->row_bytes % 16 || !aligned16(table) || !aligned16(out)) return REFORM_ERR_UNSUPPORTED;
+    RowsParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.table = table; p.out = out; p.idx = idx; p.count = count; p.err = err;
+    p.n_table = d->n_table; p.n_idx = d->n_idx; p.row_bytes = d->row_bytes; p.pieces = d->row_bytes / 16;
+    return gather_rows_launch(p, (hipStream_t)hip_stream) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 
 }  // extern "C"

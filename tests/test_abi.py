@@ -149,3 +149,38 @@ def test_embed_save_rejects_bad_arguments():
     assert call(mk(head_dim=1024, src_row_stride=1024, emb_col=0)) == 2   # 2 KB rows
     assert call(mk(emb_col=4)) == 2                       # misaligned segment
     assert call(mk(), ctypes.c_void_p(0x1008)) == 2       # misaligned source
+
+
+def test_rerotate_keys_rejects_bad_arguments():
+    lib = binding.load_library()
+    mk = lambda **kw: binding.RopeDesc(**{**dict(struct_size=ctypes.sizeof(binding.RopeDesc), dtype=1,
+                                                 n_kv_heads=8, head_dim=128, capacity=8192, n_rows=4096,
+                                                 budget=4096, rotary_dim=128, theta=10000.0), **kw})
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda d, k=fake, kept=fake: lib.reform_rerotate_keys(ctypes.byref(d), k, kept, None)
+    assert call(mk(struct_size=4)) == 1
+    assert call(mk(n_rows=5000)) == 1                     # more rows than kept_idx holds
+    assert call(mk(rotary_dim=130)) == 1
+    assert call(mk(rotary_dim=63)) == 1
+    assert call(mk(theta=1.0)) == 1
+    assert call(mk(theta=float("inf"))) == 1
+    assert call(mk(), fake, None) == 1
+    assert call(mk(rotary_dim=8)) == 2                    # half a pair set is not a 16-byte piece
+    assert call(mk(), ctypes.c_void_p(0x1004)) == 2
+
+
+def test_gather_rows_rejects_bad_arguments():
+    lib = binding.load_library()
+    mk = lambda **kw: binding.RowsDesc(**{**dict(struct_size=ctypes.sizeof(binding.RowsDesc), reserved=0,
+                                                 n_table=1000, n_idx=10, row_bytes=256), **kw})
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda d, t=fake, i=fake, o=fake: lib.reform_gather_rows(ctypes.byref(d), t, i, None, o, None, None)
+    assert call(mk(struct_size=4)) == 1
+    assert call(mk(reserved=1)) == 1
+    assert call(mk(n_table=0)) == 1
+    assert call(mk(n_idx=-1)) == 1
+    assert call(mk(), None) == 1
+    assert call(mk(), fake, None) == 1
+    assert call(mk(row_bytes=100)) == 2
+    assert call(mk(n_table=1 << 31)) == 2
+    assert call(mk(), fake, fake, ctypes.c_void_p(0x1008)) == 2

@@ -260,3 +260,13 @@ def test_combined_embedding_cosine_is_mean_of_per_head_cosines_end_to_end():
         b = qry[h].astype(np.float64)
         per_head += (b @ a.T) / (np.linalg.norm(b, axis=1)[:, None] * np.linalg.norm(a, axis=1)[None, :])
     np.testing.assert_allclose(sim, per_head / H, rtol=2e-6, atol=2e-7)      # E, U pass through float32
+
+
+def test_gather_rows_is_fancy_indexing():
+    rng = np.random.default_rng(70)
+    table = rng.integers(0, 2 ** 16, size=(50, 24), dtype=np.uint16)       # bf16-sized raw elements
+    idx = np.array([0, 3, 3, 49, 17], np.int32)
+    np.testing.assert_array_equal(oracle.gather_rows(table, idx), table[idx])
+    assert oracle.gather_rows(table, np.zeros(0, np.int32)).shape == (0, 24)
+    with pytest.raises(ValueError):
+        oracle.gather_rows(table, np.array([50], np.int32))
