@@ -23,18 +23,23 @@
  *     the H2O implementation).
  *   - Sec. 3.2, the concatenation-of-normalised-heads equation, and Sec. 3.3
  *     "Identification of significant inputs" (cosine similarity between
- *     query and context embeddings, highest scores selected, forced first
- *     and last tokens), App. C.6 "Similarity search".
+ *     query and context embeddings, max-pooling over the query tokens and
+ *     over adjacent tokens, highest scores selected, forced first and last
+ *     tokens; gathering the selected inputs for recomputation), Sec. 4.5
+ *     (pooling window), App. C.6 "Similarity search".
+ *   - Sec. 3.1, position ids made consecutive after compression (rotary keys).
  *
- * Readings taken where the paper gives no formula (each is listed in the
- * design document of this repository):
+ * Readings taken where the paper gives no formula:
  *   - eviction score of key j in KV head g = sum over the G query heads of
  *     the group and over the observing rows of the post-softmax probability
  *     p_ij (attention mass received); raw sum, no normalisation;
  *   - mask: every cache row is visible, chunk rows are causal with the
  *     diagonal included;
  *   - ties in any top selection go to the lowest index;
- *   - cosine uses the clamp  dot / max(|e||u|, eps).
+ *   - cosine uses the clamp  dot / max(|e||u|, eps);
+ *   - the pooling window is clipped at the ends of the context;
+ *   - rotary pairing is the half-split one (element c with c + rot/2);
+ *   - a zero head vector stays zero when an embedding segment is normalised.
  *
  * Parity status: every routine below is pinned by CPU tests against brute
  * force, closed forms, invariants and library routines (tests/test_oracle_*).

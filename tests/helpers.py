@@ -1,6 +1,6 @@
 """Comparators shared by the GPU parity tests.
 
-Tolerances (from the benchmark spec of this build): attention outputs and scores agree with
+Tolerances: attention outputs and scores agree with
 the fp64 oracle within 1e-5 relative error in fp32 and 2e-2 in bf16; the elementwise rule is
 |x - y| <= rtol * |y| + atol with atol = rtol * RMS(y).  Top-k index sets must match exactly
 except for candidates whose oracle score lies within that tolerance of the k-th score.
