@@ -123,13 +123,6 @@ struct TileStage {
     }
 };
 
-__device__ __forceinline__ float dot2_ones(uint32_t packed, float acc)
-{
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed),
-                                           __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
-}
-
 // p = exp2(s*c - mc) for the 32 logits a lane holds of one 64-key tile, packed to bf16 as the four
 // B operands of P.V; returns the lane's partial row sum.  The sum uses plain v_add_f32 on purpose:
 // v_dot2c_f32_bf16 (two per instruction) was measured NOT to co-execute with another wave's MFMAs
