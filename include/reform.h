@@ -227,7 +227,8 @@ reform_status reform_gather_pooled(const reform_pooled_desc *desc,
  *           [rows][heads][d] tensor can be addressed in place); dtype
  *     emb   embedding row of the chunk's first token in the [n_ctx][emb_dim] store
  *           (emb_row_stride = emb_dim elements); dtype; only columns [emb_col, emb_col+head_dim)
- *           of the n_rows rows are written
+ *           of the n_rows rows are written; with n_rows = 0 nothing is read or written and
+ *           both pointers may be NULL
  * Supported: head_dim * sizeof(dtype) a multiple of 16 and at most 1024 bytes; strides and
  * emb_col multiples of 16 bytes; src and emb 16-byte aligned.  Sums in fp32.
  */

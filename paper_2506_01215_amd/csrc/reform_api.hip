@@ -420,7 +420,7 @@ reform_status reform_embed_save_selected(const reform_embed_desc *d, const void 
     if (d->src_row_stride < d->head_dim || d->emb_row_stride < (int64_t)d->emb_col + d->head_dim)
         return REFORM_ERR_INVALID_ARG;
     if (!(d->eps > 0.f) || !std::isfinite(d->eps)) return REFORM_ERR_INVALID_ARG;
-    if (!src || !emb) return REFORM_ERR_INVALID_ARG;
+    if (d->n_rows > 0 && (!src || !emb)) return REFORM_ERR_INVALID_ARG;
     const size_t es = elt_size(d->dtype);
     const size_t row_bytes = (size_t)d->head_dim * es;
     if (row_bytes % 16 || row_bytes > 1024) return REFORM_ERR_UNSUPPORTED;
