@@ -299,9 +299,10 @@ def main():
         rows_out = torch.empty((16384, 4096), dtype=torch.bfloat16, device=dev)
         rows_times = []
         for r in range(5):
+            idx_r = ((psel.long() + r * 65537) % N).int()      # other rows every time: no cache reuse
             a, b = ev(), ev()
             a.record()
-            binding.reform_gather_rows(table, psel, out=rows_out)
+            binding.reform_gather_rows(table, idx_r, out=rows_out)
             b.record()
             torch.cuda.synchronize()
             if r >= 2:
