@@ -47,6 +47,10 @@ struct SelParams {
     float *out_val;          // nullable, values of the selected candidates
     long out_ld;
     int32_t *out_rank;       // nullable [nq][ld]: rank[t] = number of selected candidates below t
+    const int32_t *side_src; // nullable [nq][ld]: a 4-byte companion of every candidate ...
+    int32_t *side_dst;       // ... copied to [nq][out_ld] for the selected ones (same order as out_idx)
+    int *zero_extra;         // nullable: zero_extra_n more ints cleared by the histogram-clearing launch
+    int zero_extra_n;
 };
 
 struct EvictParams {

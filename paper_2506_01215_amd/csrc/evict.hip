@@ -5,8 +5,9 @@
 //   select_topk    (select.hip) exact top-B of the n candidate scores per KV head, lowest-index
 //                  ties, protected first/last slots, kept slot indices ascending
 //   evict_move_inplace K and V rows of the kept slots -> rows [0, new_len), one read + one write
-//                      per moved row, ordered by per-tile flags (row sizes dividing 16 KB)
-//   evict_move_side    the 4-byte score / pos entries through a small staging buffer
+//                      per moved row, ordered by per-tile flags (row sizes dividing 16 KB); the
+//                      4-byte score / pos entries are staged by the selection's emission pass
+//                      and written back by trailing workgroups of this kernel
 //   evict_move<..>     fallback for other row sizes: K, V, score, pos through staging
 // Rows whose slot does not change (kept_idx[r] == r, always a prefix) are not touched.
 #include "common.h"
@@ -59,26 +60,6 @@ __global__ __launch_bounds__(256) void evict_move(EvictParams p)
     else *(v4u *)cache = *(const v4u *)stage;
 }
 
-// grid (ceil(B/256), Hkv): the 4-byte score and pos entries only.
-template <bool TO_STAGE>
-__global__ __launch_bounds__(256) void evict_move_side(EvictParams p)
-{
-    const int r = blockIdx.x * 256 + threadIdx.x;
-    const int g = blockIdx.y;
-    if (r >= p.B) return;
-    const int src = p.kept[(size_t)g * p.B + r];
-    if (src == r || (unsigned)src >= (unsigned)p.n) return;
-    const size_t srow = (size_t)g * p.cap + (TO_STAGE ? src : r);
-    const size_t trow = (size_t)g * p.B + r;
-    if (TO_STAGE) {
-        p.stage_score[trow] = p.score[srow];
-        if (p.pos) p.stage_pos[trow] = p.pos[srow];
-    } else {
-        p.score[srow] = p.stage_score[trow];
-        if (p.pos) p.pos[srow] = p.stage_pos[trow];
-    }
-}
-
 // ------------------------------------------------------------------------------------------
 // In-place, single-pass compaction of the K and V rows.  Destination row r takes source row
 // kept[r] >= r, so a workgroup that writes dest rows [a, b) may destroy sources that other
@@ -102,17 +83,24 @@ constexpr int kTileBytes = 16384;
 constexpr int kSpinLimit = 1 << 22;
 constexpr int kSyncLine = 32;        // ints per 128-byte line
 
-__global__ void evict_sync_zero(int *sync, int count)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) sync[i] = 0;
-}
-
 __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
 {
     __shared__ int sh[4];
     const int tid = threadIdx.x;
     const int nstreams = p.Hkv * 2;
+    if ((int)blockIdx.x >= nstreams * p.ntile) {
+        // trailing workgroups: the 4-byte score / pos entries come back from their staging rows
+        // (filled by the selection's emission pass, which has finished before this kernel starts)
+        const int sb = blockIdx.x - nstreams * p.ntile;
+        const int per_head = (p.B + 255) / 256;
+        const int g = sb / per_head, r = (sb % per_head) * 256 + tid;
+        if (r >= p.B) return;
+        const int src = p.kept[(size_t)g * p.B + r];
+        if (src == r || (unsigned)src >= (unsigned)p.n) return;
+        p.score[(size_t)g * p.cap + r] = p.stage_score[(size_t)g * p.B + r];
+        if (p.pos) p.pos[(size_t)g * p.cap + r] = p.stage_pos[(size_t)g * p.B + r];
+        return;
+    }
     const int tr = kTileBytes / p.row_bytes;             // rows per tile
     const int pieces = p.row_bytes >> 4;
     // sync layout: [0] error word, then one ticket counter per stream (each on its own 128-byte
@@ -179,25 +167,25 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
 
 hipError_t evict_run(const EvictParams &p, hipStream_t st)
 {
-    hipError_t e = select_topk(p.sel, st);
-    if (e != hipSuccess) return e;
     const int pieces = p.row_bytes >> 4;
     if (p.sync) {
-        // side entries through staging (8 bytes per row), K/V rows in place
-        const dim3 sgrid((unsigned)((p.B + 255) / 256), p.Hkv, 1);
-        hipLaunchKernelGGL(evict_move_side<true>, sgrid, dim3(256), 0, st, p);
-        e = hipGetLastError();
+        // K/V rows in place.  The selection's own launches also clear the tickets and flags and
+        // stage the 4-byte score / pos entries of the retained slots (8 bytes per row); trailing
+        // workgroups of the move kernel bring them back.
+        SelParams sel = p.sel;
+        sel.out_val = p.stage_score;
+        sel.side_src = p.pos;
+        sel.side_dst = p.pos ? p.stage_pos : nullptr;
+        sel.zero_extra = p.sync;
+        sel.zero_extra_n = kSyncLine * (1 + p.Hkv * 2) + p.Hkv * 2 * p.ntile;
+        hipError_t e = select_topk(sel, st);
         if (e != hipSuccess) return e;
-        const int nsync = kSyncLine * (1 + p.Hkv * 2) + p.Hkv * 2 * p.ntile;
-        hipLaunchKernelGGL(evict_sync_zero, dim3((nsync + 255) / 256), dim3(256), 0, st, p.sync, nsync);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(evict_move_inplace, dim3(p.Hkv * 2 * p.ntile), dim3(256), 0, st, p);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(evict_move_side<false>, sgrid, dim3(256), 0, st, p);
+        const int side_blocks = p.Hkv * ((p.B + 255) / 256);
+        hipLaunchKernelGGL(evict_move_inplace, dim3(p.Hkv * 2 * p.ntile + side_blocks), dim3(256), 0, st, p);
         return hipGetLastError();
     }
+    hipError_t e = select_topk(p.sel, st);
+    if (e != hipSuccess) return e;
     const long items = (long)p.B * pieces;
     const dim3 grid((unsigned)((items + 255) / 256), p.Hkv, 3);
     hipLaunchKernelGGL(evict_move<true>, grid, dim3(256), 0, st, p);

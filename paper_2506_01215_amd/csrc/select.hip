@@ -2,7 +2,7 @@
 // the cache eviction (heavy hitters of the attention score, Sec. 3.1 of arXiv 2506.01215) and of
 // the gather stage (highest similarities, Sec. 3.3).
 //
-//   sel_zero      clears the digit histograms
+//   sel_zero      clears the digit histograms (and, for a caller, a few more ints in the same launch)
 //   select_hist   x3: 11 + 11 + 10 bit radix passes over the monotone uint32 image of the values;
 //                 LDS histogram per workgroup of 4096 candidates, merged with integer atomics.
 //                 From the second pass on every workgroup first re-derives the digit picked by
@@ -27,6 +27,7 @@ __global__ void sel_zero(SelParams p)
 {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < (long)p.nq * 3 * 2048) p.hist[i] = 0;
+    if (i < p.zero_extra_n) p.zero_extra[i] = 0;
 }
 
 __device__ __forceinline__ int digit_of(uint32_t u, int pass)
@@ -181,6 +182,8 @@ __global__ __launch_bounds__(256) void select_write(SelParams p)
     int32_t *orank = p.out_rank ? p.out_rank + (size_t)q * p.ld : nullptr;
     int32_t *oi = p.out_idx + (size_t)q * p.out_ld;
     float *os = p.out_val ? p.out_val + (size_t)q * p.out_ld : nullptr;
+    const int32_t *ss = p.side_src ? p.side_src + (size_t)q * p.ld : nullptr;
+    int32_t *sd = p.side_src ? p.side_dst + (size_t)q * p.out_ld : nullptr;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const long t = t0 + i;
@@ -191,6 +194,7 @@ __global__ __launch_bounds__(256) void select_write(SelParams p)
         if (keep && dest < p.k) {
             oi[dest] = (int32_t)t;
             if (os) os[dest] = val[i];
+            if (ss) sd[dest] = ss[t];
             ++dest;
         }
     }
@@ -205,7 +209,7 @@ __global__ __launch_bounds__(256) void select_write(SelParams p)
 
 hipError_t select_topk(const SelParams &p, hipStream_t st)
 {
-    const long nz = (long)p.nq * 3 * 2048;
+    const long nz = max((long)p.nq * 3 * 2048, (long)p.zero_extra_n);
     hipLaunchKernelGGL(sel_zero, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, p);
     RF_CHECK_LAUNCH();
     const dim3 sgrid(p.nblk, p.nq);
