@@ -23,6 +23,18 @@ __device__ __forceinline__ uint32_t sel_key(const SelParams &p, const float *row
     return ordered_key(row[t]);
 }
 
+__device__ __forceinline__ uint32_t sel_key_of(const SelParams &p, float v, long t)
+{
+    if (t < p.n_sink || t >= p.N - p.n_recent) return 0xffffffffu;
+    return ordered_key(v);
+}
+
+// True when the rows of `vals` can be read as aligned 16-byte quads (row pitch and base).
+__device__ __forceinline__ bool sel_rows_aligned(const SelParams &p)
+{
+    return ((p.ld & 3) == 0) && ((((uintptr_t)p.vals) & 15) == 0);
+}
+
 __global__ void sel_zero(SelParams p)
 {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -90,11 +102,26 @@ __global__ __launch_bounds__(256) void select_hist(SelParams p, int pass)
     __syncthreads();
     const float *s = p.vals + (size_t)q * p.ld;
     const long t0 = (long)blockIdx.x * kSelBlock;
-    for (int i = tid; i < kSelBlock; i += 256) {
-        const long t = t0 + i;
-        if (t < p.N) {
-            const uint32_t u = sel_key(p, s, t);
-            if (prefix_match(u, prefix, pass)) atomicAdd(&h[digit_of(u, pass)], 1);
+    if (sel_rows_aligned(p) && t0 + kSelBlock <= p.N) {
+        // full, aligned block: 16-byte loads, four candidates per lane and step
+#pragma unroll
+        for (int it = 0; it < kSelBlock / 1024; ++it) {
+            const long t = t0 + (it * 256 + tid) * 4;
+            const float4 v = *(const float4 *)(s + t);
+            const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t u = sel_key_of(p, x[j], t + j);
+                if (prefix_match(u, prefix, pass)) atomicAdd(&h[digit_of(u, pass)], 1);
+            }
+        }
+    } else {
+        for (int i = tid; i < kSelBlock; i += 256) {
+            const long t = t0 + i;
+            if (t < p.N) {
+                const uint32_t u = sel_key(p, s, t);
+                if (prefix_match(u, prefix, pass)) atomicAdd(&h[digit_of(u, pass)], 1);
+            }
         }
     }
     __syncthreads();
@@ -120,12 +147,27 @@ __global__ __launch_bounds__(256) void select_count(SelParams p)
     const float *s = p.vals + (size_t)q * p.ld;
     const long t0 = (long)blockIdx.x * kSelBlock;
     int gt = 0, eq = 0;
-    for (int i = tid; i < kSelBlock; i += 256) {
-        const long t = t0 + i;
-        if (t < p.N) {
-            const uint32_t u = sel_key(p, s, t);
-            gt += u > T;
-            eq += u == T;
+    if (sel_rows_aligned(p) && t0 + kSelBlock <= p.N) {
+#pragma unroll
+        for (int it = 0; it < kSelBlock / 1024; ++it) {
+            const long t = t0 + (it * 256 + tid) * 4;
+            const float4 v = *(const float4 *)(s + t);
+            const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t u = sel_key_of(p, x[j], t + j);
+                gt += u > T;
+                eq += u == T;
+            }
+        }
+    } else {
+        for (int i = tid; i < kSelBlock; i += 256) {
+            const long t = t0 + i;
+            if (t < p.N) {
+                const uint32_t u = sel_key(p, s, t);
+                gt += u > T;
+                eq += u == T;
+            }
         }
     }
 #pragma unroll
@@ -164,14 +206,28 @@ __global__ __launch_bounds__(256) void select_write(SelParams p)
     uint32_t u[16];
     float val[16];
     int gt_c = 0, eq_c = 0;
+    if (sel_rows_aligned(p) && t0 + 16 <= p.N) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const long t = t0 + i;
-        const bool valid = t < p.N;
-        val[i] = valid ? s[t] : 0.f;
-        u[i] = valid ? sel_key(p, s, t) : 0u;
-        gt_c += valid && u[i] > T;
-        eq_c += valid && u[i] == T;
+        for (int j = 0; j < 4; ++j) {
+            const float4 v = *(const float4 *)(s + t0 + 4 * j);
+            val[4 * j] = v.x; val[4 * j + 1] = v.y; val[4 * j + 2] = v.z; val[4 * j + 3] = v.w;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            u[i] = sel_key_of(p, val[i], t0 + i);
+            gt_c += u[i] > T;
+            eq_c += u[i] == T;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const long t = t0 + i;
+            const bool valid = t < p.N;
+            val[i] = valid ? s[t] : 0.f;
+            u[i] = valid ? sel_key(p, s, t) : 0u;
+            gt_c += valid && u[i] > T;
+            eq_c += valid && u[i] == T;
+        }
     }
     int tot;
     const int eq_before = base_eq + block256_excl_scan(eq_c, tmp, tot);
