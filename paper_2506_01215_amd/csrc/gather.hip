@@ -53,16 +53,19 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
         *(v4u *)(qs + r * QROW + c8 * 8) = v;
     }
     __syncthreads();
-    if (wave == 0) {
-        // 4 lanes per query, fixed order
-        float s = 0.f;
-        for (int c = lg; c < D; c += 4) {
-            const float x = bf16_bits_to_f32(qs[ln * QROW + c]);
-            s = fmaf(x, x, s);
+    {
+        // two queries per wave, 64 lanes per query, fixed order
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int qi = 2 * wave + h;
+            float s = 0.f;
+            for (int c = lane; c < D; c += 64) {
+                const float x = bf16_bits_to_f32(qs[qi * QROW + c]);
+                s = fmaf(x, x, s);
+            }
+            s = wave_sum(s);
+            if (lane == 0) qnorm[qi] = sqrtf(s);
         }
-        s += __shfl_xor(s, 16);
-        s += __shfl_xor(s, 32);
-        if (lg == 0) qnorm[ln] = sqrtf(s);
     }
     __syncthreads();
     const float un = qnorm[ln];
@@ -81,26 +84,29 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
         row = row < p.N ? row : p.N - 1;
         return E + (size_t)row * D + 8 * lg;
     };
-    v4u cur[kChunk], nxt[kChunk];
-    const u16 *src = row_ptr(grp);
-    auto load_chunk = [&](v4u (&dst)[kChunk], const u16 *base, int ch) {
+    // Chunks are numbered along the wave's whole stream: chunk c belongs to group
+    // grp0 + (c / nchunks) * stride, k-chunk c % nchunks.  Two chunks beyond the current one are
+    // always in flight.
+    v4u cur[kChunk], nx1[kChunk], nx2[kChunk];
+    auto load_chunk = [&](v4u (&dst)[kChunk], long c) {
+        const long g = grp + (c / nchunks) * stride;
+        if (g >= ngroups) return;
+        const u16 *base = row_ptr(g);
+        const int ch = (int)(c % nchunks);
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             const int ks = ch * kChunk + i;
             dst[i] = ks < nks ? *(const v4u *)(base + ks * 32) : (v4u){0u, 0u, 0u, 0u};
         }
     };
-    load_chunk(cur, src, 0);
+    const long my_groups = (ngroups - grp + stride - 1) / stride;
+    const long total = my_groups * nchunks;
+    load_chunk(cur, 0);
+    load_chunk(nx1, 1);
     f32x4 dot = {0.f, 0.f, 0.f, 0.f}, gram = {0.f, 0.f, 0.f, 0.f};
-    int ch = 0;
-    while (true) {
-        // prefetch the next chunk: same group, or the first chunk of this wave's next group
-        const bool last_chunk = ch + 1 == nchunks;
-        const long grp_next = last_chunk ? grp + stride : grp;
-        const bool more = grp_next < ngroups;
-        const u16 *src_next = src;
-        if (last_chunk && more) src_next = row_ptr(grp_next);
-        if (more) load_chunk(nxt, src_next, last_chunk ? 0 : ch + 1);
+    for (long c = 0; c < total; ++c) {
+        load_chunk(nx2, c + 2);
+        const int ch = (int)(c % nchunks);
         // MFMAs of the current chunk: dot products with the queries, Gram matrix of the row tile
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
@@ -112,10 +118,10 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
                 gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, a, gram, 0, 0, 0);
             }
         }
-        if (last_chunk) {
+        if (ch + 1 == nchunks) {
             // |e_r|^2 sits on the Gram diagonal: element (r, r) is in lane with ln == r, lg == r/4,
             // accumulator element r%4.  Lane (ln, lg) needs rows 4*lg + e.
-            const long row0 = grp * 16;
+            const long row0 = (grp + (c / nchunks) * stride) * 16;
             const float diag = (ln >> 2) == lg ? gram[ln & 3] : 0.f;
             float out[4];
 #pragma unroll
@@ -135,12 +141,8 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
             dot = (f32x4){0.f, 0.f, 0.f, 0.f};
             gram = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
-        if (!more) break;
 #pragma unroll
-        for (int i = 0; i < kChunk; ++i) cur[i] = nxt[i];
-        src = src_next;
-        grp = grp_next;
-        ch = last_chunk ? 0 : ch + 1;
+        for (int i = 0; i < kChunk; ++i) { cur[i] = nx1[i]; nx1[i] = nx2[i]; }
     }
 }
 
