@@ -105,7 +105,8 @@ struct PoolParams {
 
 struct GatherParams {
     const void *emb, *qry;
-    float *sim;          // [nq][N]
+    float *sim;          // [nq][sim_ld]
+    long sim_ld;         // row pitch of sim in floats (>= N)
     int32_t *topk_idx;   // [nq][k]
     float *topk_score;   // nullable
     int32_t *union_idx;  // nullable

@@ -84,29 +84,32 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
         row = row < p.N ? row : p.N - 1;
         return E + (size_t)row * D + 8 * lg;
     };
-    // Chunks are numbered along the wave's whole stream: chunk c belongs to group
-    // grp0 + (c / nchunks) * stride, k-chunk c % nchunks.  Two chunks beyond the current one are
-    // always in flight.
+    // The wave's stream is (group, k-chunk) in row-major order over its groups grp, grp + stride,
+    // ...; a load cursor runs two chunks ahead of the compute cursor, so two chunks beyond the
+    // current one are always in flight.  Both cursors advance by increments only.
     v4u cur[kChunk], nx1[kChunk], nx2[kChunk];
-    auto load_chunk = [&](v4u (&dst)[kChunk], long c) {
-        const long g = grp + (c / nchunks) * stride;
-        if (g >= ngroups) return;
-        const u16 *base = row_ptr(g);
-        const int ch = (int)(c % nchunks);
+    long l_grp = grp;                  // load cursor
+    int l_ch = 0;
+    const u16 *l_base = row_ptr(grp);
+    auto load_next = [&](v4u (&dst)[kChunk]) {
+        if (l_grp >= ngroups) return;
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
-            const int ks = ch * kChunk + i;
-            dst[i] = ks < nks ? *(const v4u *)(base + ks * 32) : (v4u){0u, 0u, 0u, 0u};
+            const int ks = l_ch * kChunk + i;
+            dst[i] = ks < nks ? *(const v4u *)(l_base + ks * 32) : (v4u){0u, 0u, 0u, 0u};
+        }
+        if (++l_ch == nchunks) {
+            l_ch = 0;
+            l_grp += stride;
+            if (l_grp < ngroups) l_base = row_ptr(l_grp);
         }
     };
-    const long my_groups = (ngroups - grp + stride - 1) / stride;
-    const long total = my_groups * nchunks;
-    load_chunk(cur, 0);
-    load_chunk(nx1, 1);
+    load_next(cur);
+    load_next(nx1);
     f32x4 dot = {0.f, 0.f, 0.f, 0.f}, gram = {0.f, 0.f, 0.f, 0.f};
-    for (long c = 0; c < total; ++c) {
-        load_chunk(nx2, c + 2);
-        const int ch = (int)(c % nchunks);
+    int ch = 0;                        // compute cursor
+    while (grp < ngroups) {
+        load_next(nx2);
         // MFMAs of the current chunk: dot products with the queries, Gram matrix of the row tile
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
         if (ch + 1 == nchunks) {
             // |e_r|^2 sits on the Gram diagonal: element (r, r) is in lane with ln == r, lg == r/4,
             // accumulator element r%4.  Lane (ln, lg) needs rows 4*lg + e.
-            const long row0 = (grp + (c / nchunks) * stride) * 16;
+            const long row0 = grp * 16;
             const float diag = (ln >> 2) == lg ? gram[ln & 3] : 0.f;
             float out[4];
 #pragma unroll
@@ -133,16 +136,23 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
                 out[e] = dot[e] / den;
             }
             if (ln < p.nq_grp) {
-                float *dst = p.sim + (size_t)(p.q0 + ln) * p.N + row0 + 4 * lg;
+                float *dst = p.sim + (size_t)(p.q0 + ln) * p.sim_ld + row0 + 4 * lg;
+                if (row0 + 16 <= p.N && ((p.sim_ld & 3) == 0) && ((((uintptr_t)p.sim) & 15) == 0)) {
+                    // one 16-byte store per lane (row0 and 4*lg are multiples of 4); four 4-byte
+                    // stores cost the kernel 15 % of its time
+                    *(f32x4 *)dst = (f32x4){out[0], out[1], out[2], out[3]};
+                } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (row0 + 4 * lg + e < p.N) dst[e] = out[e];
+                    for (int e = 0; e < 4; ++e)
+                        if (row0 + 4 * lg + e < p.N) dst[e] = out[e];
+                }
             }
             dot = (f32x4){0.f, 0.f, 0.f, 0.f};
             gram = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) { cur[i] = nx1[i]; nx1[i] = nx2[i]; }
+        if (++ch == nchunks) { ch = 0; grp += stride; }
     }
 }
 
@@ -188,7 +198,7 @@ __global__ __launch_bounds__(256) void sim_generic(GatherParams p)
                 const float dsum = wave_sum(dot[qi]);
                 float den = sqrtf(en2) * qnorm[qi];
                 den = den < p.eps ? p.eps : den;
-                if (lane == 0) p.sim[(size_t)(p.q0 + qi) * p.N + row] = dsum / den;
+                if (lane == 0) p.sim[(size_t)(p.q0 + qi) * p.sim_ld + row] = dsum / den;
             }
         }
     }

@@ -92,6 +92,11 @@ reform_status check_gather(const reform_gather_desc *d)
     return REFORM_OK;
 }
 
+// Row pitch (floats) of the similarity rows inside the workspace: a multiple of 16 bytes for any
+// n_ctx, so that the similarity kernel can store and the selection can load 16-byte quads, and
+// skewed by 4352 bytes so that the query rows a wave writes at once do not sit a power of two apart.
+long sim_pitch(int64_t n_ctx) { return (long)((n_ctx + 63) / 64 * 64 + 1088); }
+
 struct GatherLayout {
     size_t sim, hist, prefix, krem, blk, bitmap, words, total;
     int nblk, nwords, nublk;
@@ -104,7 +109,7 @@ GatherLayout gather_layout(const reform_gather_desc *d)
     L.nwords = (int)((d->n_ctx + 31) / 32);
     L.nublk = (L.nwords + 1023) / 1024;
     size_t off = 0;
-    L.sim = off;    off += align_up((size_t)d->n_query * d->n_ctx * sizeof(float));
+    L.sim = off;    off += align_up((size_t)d->n_query * sim_pitch(d->n_ctx) * sizeof(float));
     L.hist = off;   off += align_up((size_t)d->n_query * 3 * 2048 * sizeof(int));
     L.prefix = off; off += align_up((size_t)3 * d->n_query * sizeof(uint32_t));
     L.krem = off;   off += align_up((size_t)3 * d->n_query * sizeof(int));
@@ -149,7 +154,7 @@ PooledLayout pooled_layout(const reform_pooled_desc *d)
     PooledLayout L;
     L.nblk = (int)((d->n_ctx + 4095) / 4096);
     size_t off = 0;
-    L.sim = off;    off += align_up((size_t)d->n_query * d->n_ctx * sizeof(float));
+    L.sim = off;    off += align_up((size_t)d->n_query * sim_pitch(d->n_ctx) * sizeof(float));
     L.pooled = off; off += align_up((size_t)d->n_ctx * sizeof(float));
     L.hist = off;   off += align_up((size_t)3 * 2048 * sizeof(int));
     L.prefix = off; off += align_up((size_t)3 * sizeof(uint32_t));
@@ -330,6 +335,7 @@ reform_status reform_gather_similarity(const reform_gather_desc *d, const void *
     GatherParams p;
     fill_gather(p, d, emb, qry);
     p.sim = sim;
+    p.sim_ld = d->n_ctx;                          // the caller's matrix is dense
     return gather_similarity(p, d->dtype == REFORM_BF16, (hipStream_t)hip_stream) == hipSuccess
                ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
@@ -350,12 +356,13 @@ reform_status reform_gather_topk(const reform_gather_desc *d, const void *emb, c
     GatherParams p;
     fill_gather(p, d, emb, qry);
     p.sim = (float *)(ws + L.sim);
+    p.sim_ld = sim_pitch(d->n_ctx);
     p.topk_idx = topk_idx; p.topk_score = topk_score;
     p.union_idx = union_idx; p.union_count = union_count;
     p.bitmap = (uint32_t *)(ws + L.bitmap);
     p.word_cnt = (int *)(ws + L.words);
     p.nwords = L.nwords;
-    p.sel.vals = p.sim; p.sel.ld = d->n_ctx; p.sel.N = d->n_ctx;
+    p.sel.vals = p.sim; p.sel.ld = p.sim_ld; p.sel.N = d->n_ctx;
     p.sel.nq = d->n_query; p.sel.k = d->k;
     p.sel.n_sink = 0; p.sel.n_recent = 0;
     p.sel.hist = (int *)(ws + L.hist);
@@ -392,12 +399,13 @@ reform_status reform_gather_pooled(const reform_pooled_desc *d, const void *emb,
     GatherParams gp;
     fill_gather(gp, &g, emb, qry);
     gp.sim = (float *)(ws + L.sim);
+    gp.sim_ld = sim_pitch(d->n_ctx);
     if (gather_similarity(gp, d->dtype == REFORM_BF16, st) != hipSuccess) return REFORM_ERR_RUNTIME;
     PoolParams p;
     std::memset(&p, 0, sizeof(p));
     p.sim = gp.sim;
     p.pooled = pooled ? pooled : (float *)(ws + L.pooled);
-    p.N = d->n_ctx; p.ld = d->n_ctx; p.nq = d->n_query; p.window = d->pool_window;
+    p.N = d->n_ctx; p.ld = gp.sim_ld; p.nq = d->n_query; p.window = d->pool_window;
     p.sel.vals = p.pooled; p.sel.ld = d->n_ctx; p.sel.N = d->n_ctx;
     p.sel.nq = 1; p.sel.k = d->budget;
     p.sel.n_sink = d->n_head_keep; p.sel.n_recent = d->n_tail_keep;
