@@ -8,11 +8,13 @@
 //                    needs the final normaliser of every row, so QK^T is formed a second time; the
 //                    probabilities are never stored.
 //
-// Both kernels compute the TRANSPOSED logit tile  S^T = K Q^T  with v_mfma_f32_32x32x16_bf16:
-// a lane then owns one query column (lane % 32) and 16 key rows, so the softmax row statistics
-// are per-lane scalars (one exchange with lane ^ 32), and the probabilities are already laid out
-// as the B operand of  O^T = V^T P^T  once the contraction index is permuted consistently on
-// the V side (V is written into LDS transposed, with that permutation).
+// Both kernels compute the TRANSPOSED logit tile  S^T = K Q^T: a lane then owns one query column
+// and a few key rows, so the softmax row statistics are per-lane scalars (exchanged across the
+// lane groups once), and the probabilities are already laid out as the B operand of
+// O^T = V^T P^T  once the contraction index is permuted consistently on the V side (V is written
+// into LDS transposed, with that permutation).  The forward kernel uses
+// v_mfma_f32_16x16x32_bf16, the score kernel v_mfma_f32_32x32x16_bf16 (it is bound by VALU issue,
+// where the larger tile's fewer MFMA instructions matter more than its higher energy per flop).
 //
 // MFMA 32x32x16 operand layout (wave64): A[m][k]: lane l holds m = l%32, k = 8*(l/32)..+7;
 // B[k][n]: lane l holds n = l%32, k = 8*(l/32)..+7;  C[m][n]: lane l holds n = l%32 and, in
@@ -29,29 +31,35 @@ __device__ __forceinline__ f32x16 mfma32(v4u a, v4u b, f32x16 c)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
 }
 
-// Position of key (within a 64-key tile) inside a transposed V row in LDS.  Within each group of
-// 16 keys, key 8h + 4g + r sits at 8g + 4h + r, so that lane group g = lane/32 finds the 8 keys
-// whose probabilities it holds in accumulator elements 8*(t%2)..+7 as 16 contiguous bytes.
+// Position of key (within a 64-key tile) inside a transposed V row in LDS.  The forward kernel
+// contracts 32 keys per P.V MFMA; lane group g = lane/16 holds, for its query, the probabilities
+// of keys 16*kb + 4g + r (r = 0..3) of every 16-key block kb, and feeds blocks 2*kp and 2*kp+1 as
+// the eight B elements of key pair kp.  Key 32*kp + 16*h + 4*g + r therefore sits at
+// 32*kp + 8*g + 4*h + r, so that the matching V^T elements are 16 contiguous bytes.
 __device__ __forceinline__ int vt_pos(int key)
 {
-    const int k16 = key & 15;
-    return (key & ~15) + ((k16 & 4) << 1) + ((k16 & 8) >> 1) + (k16 & 3);
+    return (key & 32) + ((key & 12) << 1) + ((key & 16) >> 2) + (key & 3);
 }
 
 // ------------------------------------------------------------------------------------------
 // Global -> register -> LDS staging of one 64-key K/V tile by a workgroup of NT threads.
-// K rows are copied as they are (row pitch D+8 elements).  V is transposed: thread (v_dq, v_k0)
-// holds an 8-wide d slice of PIECES consecutive keys and writes, for each of the 8 d rows,
-// PIECES consecutive bf16.  Inside a V^T row (64 keys = eight 16-byte chunks + pad) the chunk
-// index is XOR-ed with (row/32)%8.  Measured on gfx950: with the 144-byte pitch alone a
-// fragment read costs ~5 clk per wave but the transposing writes collide 16-way (32 clk per
-// dword); this swizzle is constant over a fragment read (so reads stay conflict-free) and cuts
-// the write cost to ~8 clk.  Finer swizzles (row/8, row/16) made the reads 2-3x slower.
+// K rows are copied as they are.  V is transposed: thread (v_dq, v_k0) holds an 8-wide d slice of
+// PIECES consecutive keys and writes, for each of the 8 d rows, PIECES consecutive bf16.
+//
+// LDS layout, measured on gfx950: a ds_read_b128 is served half a wave at a time and is free of
+// bank conflicts when the 32 lanes touch 32 different 16-byte slots modulo 512 bytes.  The
+// fragment reads of the forward kernel have 16-lane row groups (lane%16 = row, lane/16 = 16-byte
+// piece), so a half wave reads 16 rows x 2 adjacent pieces: the row pitch must be an odd multiple
+// of 32 bytes -- 288 bytes for K rows (D = 128), 160 bytes for V^T rows.  With the pitches of the
+// 32-lane layout (272 / 144 bytes) this read pattern showed 3.7x the bank-conflict cycles.
+// Inside a V^T row (64 keys = eight 16-byte chunks + pad) the chunk index is XOR-ed with
+// (row/16)%8: constant over a fragment read, and it spreads the transposing 4-byte writes, which
+// otherwise collide 8- to 16-way, over all banks.
 template <int D, int NT>
 struct TileStage {
     static constexpr int BN = 64;
-    static constexpr int KROW = D + 8;
-    static constexpr int VROW = BN + 8;
+    static constexpr int KROW = D + 16;
+    static constexpr int VROW = BN + 16;
     static constexpr int C8 = D / 8;
     static constexpr int PIECES = BN * C8 / NT;
     static_assert(PIECES == 1 || PIECES == 2 || PIECES == 4, "tile/threads mismatch");
@@ -69,7 +77,7 @@ struct TileStage {
         v_goff = (uint32_t)(v_k0 * D + v_dq * 8) * 2u;
         k_loff = (uint32_t)(k_row * KROW + (tid % C8) * 8);
         const int pos = vt_pos(v_k0);
-        const int sw = (v_dq >> 2) & 7;
+        const int sw = (v_dq >> 1) & 7;
         v_loff = (uint32_t)(v_dq * 8 * VROW + ((((pos >> 3) ^ sw) << 3) | (pos & 7)));
     }
     // Kt, Vt: tile base pointers (uniform); rows_left = n - j0 (>= 1).  Piece i of K sits NT/C8 rows
@@ -123,31 +131,32 @@ struct TileStage {
     }
 };
 
-// p = exp2(s*c - mc) for the 32 logits a lane holds of one 64-key tile, packed to bf16 as the four
-// B operands of P.V; returns the lane's partial row sum.  The sum uses plain v_add_f32 on purpose:
-// v_dot2c_f32_bf16 (two per instruction) was measured NOT to co-execute with another wave's MFMAs
-// on gfx950 (a wave of cvt+dot2 next to a wave of MFMAs takes the sum of their solo times), while
-// v_fma / v_add / v_exp / v_cvt_pk do overlap almost completely.
-__device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, float mc, v4u (&pb)[4])
+__device__ __forceinline__ f32x4 mfma16(v4u a, v4u b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+}
+
+// p = exp2(s*c - mc) for the 16 logits a lane holds of one query and one 64-key tile (four 16-key
+// blocks x 4 keys), packed to bf16 as the two B operands of P.V (key pairs 0 and 1); returns the
+// lane's partial row sum.  Plain v_add_f32 on purpose: v_dot2c_f32_bf16 was measured NOT to
+// co-execute with another wave's MFMAs on gfx950, while v_fma / v_add / v_exp / v_cvt_pk do.
+__device__ __forceinline__ float softmax_row(const f32x4 (&s)[4], float c, float mc, v4u (&pb)[2])
 {
     float rs = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-        float pv[16];
+    for (int kp = 0; kp < 2; ++kp) {
+        float pv[8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][e], c, -mc));
-            rs += pv[e];
+        for (int j = 0; j < 8; ++j) {
+            pv[j] = __builtin_amdgcn_exp2f(fmaf(s[2 * kp + (j >> 2)][j & 3], c, -mc));
+            rs += pv[j];
         }
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            v4u w;
-            w.x = pack_bf16x2(pv[8 * hh + 0], pv[8 * hh + 1]);
-            w.y = pack_bf16x2(pv[8 * hh + 2], pv[8 * hh + 3]);
-            w.z = pack_bf16x2(pv[8 * hh + 4], pv[8 * hh + 5]);
-            w.w = pack_bf16x2(pv[8 * hh + 6], pv[8 * hh + 7]);
-            pb[kb * 2 + hh] = w;
-        }
+        v4u w;
+        w.x = pack_bf16x2(pv[0], pv[1]);
+        w.y = pack_bf16x2(pv[2], pv[3]);
+        w.z = pack_bf16x2(pv[4], pv[5]);
+        w.w = pack_bf16x2(pv[6], pv[7]);
+        pb[kp] = w;
     }
     return rs;
 }
@@ -156,15 +165,22 @@ __device__ __forceinline__ float softmax_tile(const f32x16 (&s)[2], float c, flo
 // waves of a workgroup cover `gp` query heads of one KV group times 8/gp row slabs, so the K/V
 // tiles staged in LDS (double-buffered, one barrier per 64-key tile) serve every wave.
 //
-// Measured on gfx950 with random bf16 operands this kernel is limited by the power budget, not by
-// instruction issue: the shader clock falls to about 1.8 GHz under it (2.35 GHz with all-zero
-// operands, same cycle count), and the MFMA pipe is busy 56 % of the cycles.  Wall time follows
-// the energy of the launch, so the kernel is built to keep the instruction count and the data
-// movement per tile small rather than to chase a particular interleaving:
+// MFMA shape: v_mfma_f32_16x16x32_bf16 (A[m][k]: lane l holds m = l%16, k = 8*(l/16)..+7; B[k][n]:
+// n = l%16, same k; C[m][n]: n = l%16, m = 4*(l/16) + e).  Measured on gfx950 with random bf16
+// operands the matrix pipe is limited by the power budget, and this shape sustains 2.03 PFLOP/s
+// against 1.83 PFLOP/s for 32x32x16 (both reach 2.36-2.39 with all-zero operands): it moves half
+// the accumulator data per flop.  S^T = K Q^T is formed per 16-key block and 16-query block: a lane
+// owns one query column (lane % 16) of each of the wave's two query blocks and, per key block, the
+// four keys 4*(lane/16)..+3; row statistics are per-lane scalars reduced over lane/16 once at
+// the end, and the probabilities are already the B operand of O^T = V^T P^T (see vt_pos).
+//
+// Wall time follows the energy of the launch (the shader clock falls to about 1.8 GHz under
+// this kernel with random data), so the kernel keeps the instruction count and the data
+// movement per tile small:
 //   - no row maximum on the fast path: probabilities are formed against the current reference
 //     m_run; if a row outgrew it by more than kBigSum (or m_run is still -inf) the tile sum of
 //     that row is huge / inf / NaN, and only then the whole wave recomputes with the true maximum
-//     and rescales its 16*DB accumulators once;
+//     and rescales its accumulators once;
 //   - scale*log2(e) folded into one v_fma per logit, v_exp_f32 directly, packed bf16 converts;
 //   - tile addresses are a uniform base plus per-thread constants computed once.
 constexpr float kBigSum = 65536.0f;
@@ -173,7 +189,7 @@ constexpr int kFwdWaves = 8;
 template <int D>
 constexpr size_t fwd_lds_bytes()
 {
-    return sizeof(u16) * (size_t)(2 * 64 * (D + 8) + 2 * D * (64 + 8));
+    return sizeof(u16) * (size_t)(2 * 64 * (D + 16) + 2 * D * (64 + 16));
 }
 
 template <int D>
@@ -181,13 +197,14 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 {
     constexpr int NW = kFwdWaves;
     constexpr int NT = NW * 64;
-    constexpr int KS = D / 16;           // MFMA k-steps of Q.K^T
-    constexpr int DB = D / 32;           // 32-wide output blocks of P.V
+    constexpr int KS = D / 32;           // MFMA k-steps of Q.K^T
+    constexpr int DB = D / 16;           // 16-wide output blocks of P.V
     using Stage = TileStage<D, NT>;
     constexpr int BN = Stage::BN, KROW = Stage::KROW, VROW = Stage::VROW;
     constexpr int KTILE = BN * KROW, VTILE = D * VROW;
     constexpr int kWin = 8;              // fragment prefetch distance (register quads)
-    constexpr int NV = 4 * DB, NK = 2 * KS;
+    constexpr int NK = 4 * KS;           // K fragments per tile  (key block, k-step)
+    constexpr int NV = 2 * DB;           // V^T fragments per tile (key pair, d block)
 
     extern __shared__ __attribute__((aligned(16))) u16 smem[];
     u16 *ldsK = smem;                          // [2][KTILE]
@@ -196,8 +213,8 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int ln = lane & 31;
-    const int lg = lane >> 5;
+    const int ln = lane & 15;
+    const int lg = lane >> 4;
 
     // block -> (kv head, head subgroup, row block); heavy (late) row blocks first
     const int bid = blockIdx.x;
@@ -214,27 +231,30 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
     const u16 *Kg = (const u16 *)p.k + (size_t)kvh * p.cap * D;
     const u16 *Vg = (const u16 *)p.v + (size_t)kvh * p.cap * D;
 
-    // Q^T operands stay in registers for the whole pass
-    v4u qreg[KS];
+    // Q^T operands of the wave's two 16-row query blocks stay in registers for the whole pass
+    v4u qreg[2][KS];
     {
         const u16 *Qh = (const u16 *)p.q + (size_t)head * p.q_hs;
-        int row = w0 + ln;
-        row = row < p.Ct ? row : p.Ct - 1;
-        const u16 *src = Qh + (size_t)row * p.q_rs + 8 * lg;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qreg[ks] = *(const v4u *)(src + ks * 16);
+        for (int nb = 0; nb < 2; ++nb) {
+            int row = w0 + 16 * nb + ln;
+            row = row < p.Ct ? row : p.Ct - 1;
+            const u16 *src = Qh + (size_t)row * p.q_rs + 8 * lg;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) qreg[nb][ks] = *(const v4u *)(src + ks * 32);
+        }
     }
 
     const int wg_last_row = min(rb * rwg + rwg, p.Ct) - 1;
     const int ntiles = (p.M + wg_last_row) / BN + 1;
     const int wave_last_key = (w0 < p.Ct) ? p.M + min(w0 + 32, p.Ct) - 1 : -1;
 
-    f32x16 o[DB];
-    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 o[2][DB];
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
+        for (int db = 0; db < DB; ++db) o[nb][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     const float c = p.scale * kLog2e;
     // per-lane fragment offsets (elements) inside a K tile / V^T tile
@@ -254,73 +274,84 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
         if (j0 <= wave_last_key) {
             const u16 *sk = ldsK + buf * KTILE + k_frag0;
             const u16 *sv = ldsV + buf * VTILE + v_frag0;
-            auto kfrag = [&](int i) -> v4u {     // i = 2*ks + kb
-                return *(const v4u *)(sk + (i & 1) * 32 * KROW + (i >> 1) * 16);
+            auto kfrag = [&](int i) -> v4u {     // i = 4*ks + kb: keys 16*kb + ln, d 32*ks + 8*lg..+7
+                return *(const v4u *)(sk + (i & 3) * 16 * KROW + (i >> 2) * 32);
             };
-            auto vfrag = [&](int i) -> v4u {     // i = DB*t16 + db; XOR swizzle (row/32)%8 = db
-                const int t16 = i / DB, db = i % DB;
-                return *(const v4u *)(sv + db * 32 * VROW + ((2 * t16 + lg) ^ (db & 7)) * 8);
+            auto vfrag = [&](int i) -> v4u {     // i = DB*kp + db: d 16*db + ln, key pair kp;
+                const int kp = i / DB, db = i % DB;      // chunk XOR-ed with (row/16)%8 = db%8
+                return *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
             };
-            // ---- S^T = K Q^T; fragments stream through a rolling window of kWin register quads;
-            // the window is refilled with the first V^T fragments while the last MFMAs run
+            // ---- S^T = K Q^T; fragments stream through a rolling window of kWin register quads,
+            // each feeding the MFMAs of both query blocks; the window is refilled with the first
+            // V^T fragments while the last MFMAs run
             v4u fw[kWin];
 #pragma unroll
             for (int i = 0; i < kWin; ++i) fw[i] = kfrag(i);
-            f32x16 s[2];
+            f32x4 s[2][4];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+                for (int kb = 0; kb < 4; ++kb) s[nb][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int f = 0; f < NK; ++f) {
-                s[f & 1] = mfma32(fw[f % kWin], qreg[f >> 1], s[f & 1]);
+                s[0][f & 3] = mfma16(fw[f % kWin], qreg[0][f >> 2], s[0][f & 3]);
+                s[1][f & 3] = mfma16(fw[f % kWin], qreg[1][f >> 2], s[1][f & 3]);
                 const int g = f + kWin;
                 fw[f % kWin] = g < NK ? kfrag(g) : vfrag(g - NK);
             }
             __builtin_amdgcn_sched_group_barrier(0x100, kWin, 0);
 #pragma unroll
             for (int f = 0; f < NK; ++f) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
             // ---- causal mask on tiles that reach past the first row of this wave
             if (j0 + BN - 1 > p.M + w0) {
                 asm volatile("; mask path" ::: "memory");      // diagonal tiles only: keep out of line
-                const int lim = p.M + w0 + ln - j0;   // key offset <= lim is visible
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int nb = 0; nb < 2; ++nb) {
+                    const int lim = p.M + w0 + 16 * nb + ln - j0;   // key offset <= lim is visible
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int koff = kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
-                        if (koff > lim) s[kb][e] = -INFINITY;
-                    }
+                    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (kb * 16 + 4 * lg + e > lim) s[nb][kb][e] = -INFINITY;
+                }
             }
             // ---- softmax (see the header comment)
-            v4u pb[4];
-            float rs = softmax_tile(s, c, m_run * c, pb);
-            if (__builtin_amdgcn_ballot_w64(!(rs < kBigSum)) != 0ull) {
+            v4u pb[2][2];
+            float rs0 = softmax_row(s[0], c, m_run[0] * c, pb[0]);
+            float rs1 = softmax_row(s[1], c, m_run[1] * c, pb[1]);
+            if (__builtin_amdgcn_ballot_w64(!(rs0 < kBigSum) || !(rs1 < kBigSum)) != 0ull) {
                 asm volatile("; rescale path" ::: "memory");   // keeps this rare block out of line
-                float mx = s[0][0];
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int nb = 0; nb < 2; ++nb) {
+                    float mx = s[nb][0][0];
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kb][e]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(mx, m_run);
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                m_run = m_new;
-                l_run *= alpha;
+                    for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, s[nb][kb][e]);
+                    mx = fmaxf(mx, __shfl_xor(mx, 16));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    const float m_new = fmaxf(mx, m_run[nb]);
+                    const float alpha = __builtin_amdgcn_exp2f((m_run[nb] - m_new) * c);
+                    m_run[nb] = m_new;
+                    l_run[nb] *= alpha;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-                rs = softmax_tile(s, c, m_run * c, pb);
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[nb][db][e] *= alpha;
+                }
+                rs0 = softmax_row(s[0], c, m_run[0] * c, pb[0]);
+                rs1 = softmax_row(s[1], c, m_run[1] * c, pb[1]);
             }
-            l_run += rs;
-            // ---- O^T += V^T P^T (DB independent chains), rest of the V^T fragments
+            l_run[0] += rs0;
+            l_run[1] += rs1;
+            // ---- O^T += V^T P^T, rest of the V^T fragments
 #pragma unroll
             for (int f = 0; f < NV; ++f) {
-                o[f % DB] = mfma32(fw[f % kWin], pb[f / DB], o[f % DB]);
+                o[0][f % DB] = mfma16(fw[f % kWin], pb[0][f / DB], o[0][f % DB]);
+                o[1][f % DB] = mfma16(fw[f % kWin], pb[1][f / DB], o[1][f % DB]);
                 if (f + kWin < NV) fw[f % kWin] = vfrag(f + kWin);
             }
         }
@@ -337,21 +368,23 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 
     if (wave_last_key < 0) return;
     u16 *Oh = (u16 *)p.out + (size_t)head * p.o_hs;
-    const int row = w0 + ln;
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (row >= p.Ct) return;
-    const float inv = 1.0f / l_tot;
-    u16 *dst = Oh + (size_t)row * p.o_rs;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int nb = 0; nb < 2; ++nb) {
+        const int row = w0 + 16 * nb + ln;
+        float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 16);
+        l_tot += __shfl_xor(l_tot, 32);
+        if (row >= p.Ct) continue;
+        const float inv = 1.0f / l_tot;
+        u16 *dst = Oh + (size_t)row * p.o_rs;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int db = 0; db < DB; ++db) {
             v2u w;
-            w.x = pack_bf16x2(o[db][4 * b + 0] * inv, o[db][4 * b + 1] * inv);
-            w.y = pack_bf16x2(o[db][4 * b + 2] * inv, o[db][4 * b + 3] * inv);
-            *(v2u *)(dst + db * 32 + 8 * b + 4 * lg) = w;
+            w.x = pack_bf16x2(o[nb][db][0] * inv, o[nb][db][1] * inv);
+            w.y = pack_bf16x2(o[nb][db][2] * inv, o[nb][db][3] * inv);
+            *(v2u *)(dst + db * 16 + 4 * lg) = w;
         }
-    if (lg == 0) p.lse[(size_t)head * p.Ct + row] = (m_run * c + __builtin_amdgcn_logf(l_tot)) * kLn2;
+        if (lg == 0) p.lse[(size_t)head * p.Ct + row] = (m_run[nb] * c + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
