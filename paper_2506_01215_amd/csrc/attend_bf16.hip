@@ -354,6 +354,11 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
                 o[1][f % DB] = mfma16(fw[f % kWin], pb[1][f / DB], o[1][f % DB]);
                 if (f + kWin < NV) fw[f % kWin] = vfrag(f + kWin);
             }
+#pragma unroll
+            for (int f = 0; f < NV; ++f) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                if (f + kWin < NV) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
         }
         // stage tile t+1 (already in registers) into the other buffer, prefetch tile t+2
         if (t + 1 < ntiles) {
