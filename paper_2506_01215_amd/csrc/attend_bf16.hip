@@ -189,7 +189,7 @@ constexpr int kFwdWaves = 8;
 template <int D>
 constexpr size_t fwd_lds_bytes()
 {
-    return sizeof(u16) * (size_t)(2 * 64 * (D + 16) + 2 * D * (64 + 16));
+    return sizeof(u16) * (size_t)(2 * 64 * (D + 16) + 3 * D * (64 + 16));
 }
 
 template <int D>
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 
     extern __shared__ __attribute__((aligned(16))) u16 smem[];
     u16 *ldsK = smem;                          // [2][KTILE]
-    u16 *ldsV = smem + 2 * KTILE;              // [2][VTILE]
+    u16 *ldsV = smem + 2 * KTILE;              // [3][VTILE]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -268,107 +268,190 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
     if (ntiles > 1) st.load(Kg + BN * D, Vg + BN * D, p.n - BN);
     __syncthreads();
 
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        const int j0 = t * BN;
-        if (j0 <= wave_last_key) {
-            const u16 *sk = ldsK + buf * KTILE + k_frag0;
-            const u16 *sv = ldsV + buf * VTILE + v_frag0;
-            auto kfrag = [&](int i) -> v4u {     // i = 4*ks + kb: keys 16*kb + ln, d 32*ks + 8*lg..+7
-                return *(const v4u *)(sk + (i & 3) * 16 * KROW + (i >> 2) * 32);
-            };
-            auto vfrag = [&](int i) -> v4u {     // i = DB*kp + db: d 16*db + ln, key pair kp;
-                const int kp = i / DB, db = i % DB;      // chunk XOR-ed with (row/16)%8 = db%8
-                return *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
-            };
-            // ---- S^T = K Q^T; fragments stream through a rolling window of kWin register quads,
-            // each feeding the MFMAs of both query blocks; the window is refilled with the first
-            // V^T fragments while the last MFMAs run
-            v4u fw[kWin];
+    // Two waves share a SIMD (wave w and w + NW/2), and the barrier per tile keeps them in step.
+    // To make one wave's MFMAs meet the other's softmax, the waves of the upper half run their
+    // O^T += V^T P^T one tile late: iteration t does P.V of tile t-1 first, then Q.K^T and the
+    // softmax of tile t, keeping the probabilities in registers across the barrier.  V therefore
+    // lives in three LDS slots (tile u in slot u%3), K in two.
+    const bool lag = wave >= NW / 2;
+    const int tl = wave_last_key >= 0 ? wave_last_key / BN : -1;      // last tile this wave needs
+    v4u pb[2][2];
+    int vslot = 0;                                                    // t mod 3
+
+    auto mask_tile = [&](f32x4 (&s)[2][4], int j0) {
+        if (j0 + BN - 1 > p.M + w0) {
+            asm volatile("; mask path" ::: "memory");      // diagonal tiles only: keep out of line
 #pragma unroll
-            for (int i = 0; i < kWin; ++i) fw[i] = kfrag(i);
-            f32x4 s[2][4];
+            for (int nb = 0; nb < 2; ++nb) {
+                const int lim = p.M + w0 + 16 * nb + ln - j0;   // key offset <= lim is visible
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+                for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb) s[nb][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int f = 0; f < NK; ++f) {
-                s[0][f & 3] = mfma16(fw[f % kWin], qreg[0][f >> 2], s[0][f & 3]);
-                s[1][f & 3] = mfma16(fw[f % kWin], qreg[1][f >> 2], s[1][f & 3]);
-                const int g = f + kWin;
-                fw[f % kWin] = g < NK ? kfrag(g) : vfrag(g - NK);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x100, kWin, 0);
-#pragma unroll
-            for (int f = 0; f < NK; ++f) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            // ---- causal mask on tiles that reach past the first row of this wave
-            if (j0 + BN - 1 > p.M + w0) {
-                asm volatile("; mask path" ::: "memory");      // diagonal tiles only: keep out of line
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    const int lim = p.M + w0 + 16 * nb + ln - j0;   // key offset <= lim is visible
-#pragma unroll
-                    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (kb * 16 + 4 * lg + e > lim) s[nb][kb][e] = -INFINITY;
-                }
-            }
-            // ---- softmax (see the header comment)
-            v4u pb[2][2];
-            float rs0 = softmax_row(s[0], c, m_run[0] * c, pb[0]);
-            float rs1 = softmax_row(s[1], c, m_run[1] * c, pb[1]);
-            if (__builtin_amdgcn_ballot_w64(!(rs0 < kBigSum) || !(rs1 < kBigSum)) != 0ull) {
-                asm volatile("; rescale path" ::: "memory");   // keeps this rare block out of line
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    float mx = s[nb][0][0];
-#pragma unroll
-                    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, s[nb][kb][e]);
-                    mx = fmaxf(mx, __shfl_xor(mx, 16));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const float m_new = fmaxf(mx, m_run[nb]);
-                    const float alpha = __builtin_amdgcn_exp2f((m_run[nb] - m_new) * c);
-                    m_run[nb] = m_new;
-                    l_run[nb] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[nb][db][e] *= alpha;
-                }
-                rs0 = softmax_row(s[0], c, m_run[0] * c, pb[0]);
-                rs1 = softmax_row(s[1], c, m_run[1] * c, pb[1]);
-            }
-            l_run[0] += rs0;
-            l_run[1] += rs1;
-            // ---- O^T += V^T P^T, rest of the V^T fragments
-#pragma unroll
-            for (int f = 0; f < NV; ++f) {
-                o[0][f % DB] = mfma16(fw[f % kWin], pb[0][f / DB], o[0][f % DB]);
-                o[1][f % DB] = mfma16(fw[f % kWin], pb[1][f / DB], o[1][f % DB]);
-                if (f + kWin < NV) fw[f % kWin] = vfrag(f + kWin);
-            }
-#pragma unroll
-            for (int f = 0; f < NV; ++f) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                if (f + kWin < NV) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int e = 0; e < 4; ++e)
+                        if (kb * 16 + 4 * lg + e > lim) s[nb][kb][e] = -INFINITY;
             }
         }
-        // stage tile t+1 (already in registers) into the other buffer, prefetch tile t+2
+    };
+    // probabilities of one tile into pb, running sums; the rare rescale is kept out of line
+    auto softmax_phase = [&](f32x4 (&s)[2][4]) {
+        float rs0 = softmax_row(s[0], c, m_run[0] * c, pb[0]);
+        float rs1 = softmax_row(s[1], c, m_run[1] * c, pb[1]);
+        if (__builtin_amdgcn_ballot_w64(!(rs0 < kBigSum) || !(rs1 < kBigSum)) != 0ull) {
+            asm volatile("; rescale path" ::: "memory");
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                float mx = s[nb][0][0];
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) mx = fmaxf(mx, s[nb][kb][e]);
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(mx, m_run[nb]);
+                const float alpha = __builtin_amdgcn_exp2f((m_run[nb] - m_new) * c);
+                m_run[nb] = m_new;
+                l_run[nb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[nb][db][e] *= alpha;
+            }
+            rs0 = softmax_row(s[0], c, m_run[0] * c, pb[0]);
+            rs1 = softmax_row(s[1], c, m_run[1] * c, pb[1]);
+        }
+        l_run[0] += rs0;
+        l_run[1] += rs1;
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        const int j0 = t * BN;
+        const u16 *sk = ldsK + (t & 1) * KTILE + k_frag0;
+        auto kfrag = [&](int i) -> v4u {         // i = 4*ks + kb: keys 16*kb + ln, d 32*ks + 8*lg..+7
+            return *(const v4u *)(sk + (i & 3) * 16 * KROW + (i >> 2) * 32);
+        };
+        if (!lag) {
+            if (t <= tl) {
+                asm volatile("; in-step wave" ::: "memory");
+                const u16 *sv = ldsV + vslot * VTILE + v_frag0;
+                auto vfrag = [&](int i) -> v4u { // i = DB*kp + db: d 16*db + ln, key pair kp;
+                    const int kp = i / DB, db = i % DB;  // chunk XOR-ed with (row/16)%8 = db%8
+                    return *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
+                };
+                // ---- S^T = K Q^T; fragments stream through a rolling window of kWin register
+                // quads, each feeding the MFMAs of both query blocks; the window is refilled with
+                // the first V^T fragments while the last MFMAs run
+                v4u fw[kWin];
+#pragma unroll
+                for (int i = 0; i < kWin; ++i) fw[i] = kfrag(i);
+                f32x4 s[2][4];
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int kb = 0; kb < 4; ++kb) s[nb][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NK; ++f) {
+                    s[0][f & 3] = mfma16(fw[f % kWin], qreg[0][f >> 2], s[0][f & 3]);
+                    s[1][f & 3] = mfma16(fw[f % kWin], qreg[1][f >> 2], s[1][f & 3]);
+                    const int g = f + kWin;
+                    fw[f % kWin] = g < NK ? kfrag(g) : vfrag(g - NK);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, kWin, 0);
+#pragma unroll
+                for (int f = 0; f < NK; ++f) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                mask_tile(s, j0);
+                softmax_phase(s);
+                // ---- O^T += V^T P^T, rest of the V^T fragments
+#pragma unroll
+                for (int f = 0; f < NV; ++f) {
+                    o[0][f % DB] = mfma16(fw[f % kWin], pb[0][f / DB], o[0][f % DB]);
+                    o[1][f % DB] = mfma16(fw[f % kWin], pb[1][f / DB], o[1][f % DB]);
+                    if (f + kWin < NV) fw[f % kWin] = vfrag(f + kWin);
+                }
+#pragma unroll
+                for (int f = 0; f < NV; ++f) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    if (f + kWin < NV) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+            }
+        } else {
+            const bool do_pv = t >= 1 && t - 1 <= tl, do_qk = t <= tl;
+            if (do_pv || do_qk) {
+                asm volatile("; lagging wave" ::: "memory");
+                const u16 *sv = ldsV + (vslot == 0 ? 2 : vslot - 1) * VTILE + v_frag0;   // tile t-1
+                auto vfrag = [&](int i) -> v4u {
+                    const int kp = i / DB, db = i % DB;
+                    return *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
+                };
+                v4u fw[kWin];
+                if (do_pv) {
+                    // ---- O^T += V^T P^T of the previous tile; the window is refilled with the
+                    // first K fragments of this tile while the last MFMAs run
+#pragma unroll
+                    for (int i = 0; i < kWin; ++i) fw[i] = vfrag(i);
+#pragma unroll
+                    for (int f = 0; f < NV; ++f) {
+                        o[0][f % DB] = mfma16(fw[f % kWin], pb[0][f / DB], o[0][f % DB]);
+                        o[1][f % DB] = mfma16(fw[f % kWin], pb[1][f / DB], o[1][f % DB]);
+                        const int g = f + kWin;
+                        fw[f % kWin] = g < NV ? vfrag(g) : kfrag(g - NV);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x100, kWin, 0);
+#pragma unroll
+                    for (int f = 0; f < NV; ++f) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < kWin; ++i) fw[i] = kfrag(i);
+                }
+                if (do_qk) {
+                    f32x4 s[2][4];
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                        for (int kb = 0; kb < 4; ++kb) s[nb][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int f = 0; f < NK; ++f) {
+                        s[0][f & 3] = mfma16(fw[f % kWin], qreg[0][f >> 2], s[0][f & 3]);
+                        s[1][f & 3] = mfma16(fw[f % kWin], qreg[1][f >> 2], s[1][f & 3]);
+                        if (f + kWin < NK) fw[f % kWin] = kfrag(f + kWin);
+                    }
+#pragma unroll
+                    for (int f = 0; f < NK; ++f) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        if (f + kWin < NK) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    mask_tile(s, j0);
+                    softmax_phase(s);
+                }
+            }
+        }
+        // stage tile t+1 (already in registers), prefetch tile t+2
         if (t + 1 < ntiles) {
-            st.store(ldsK + (buf ^ 1) * KTILE, ldsV + (buf ^ 1) * VTILE);
+            const int vnext = vslot == 2 ? 0 : vslot + 1;
+            st.store(ldsK + ((t + 1) & 1) * KTILE, ldsV + vnext * VTILE);
             if (t + 2 < ntiles) {
                 const size_t off = (size_t)(j0 + 2 * BN) * D;
                 st.load(Kg + off, Vg + off, p.n - (j0 + 2 * BN));
             }
         }
+        vslot = vslot == 2 ? 0 : vslot + 1;
         __syncthreads();
+    }
+    if (lag && tl == ntiles - 1) {
+        // the lagging waves still owe the P.V of their last tile (slot (ntiles-1) % 3)
+        const u16 *sv = ldsV + (vslot == 0 ? 2 : vslot - 1) * VTILE + v_frag0;
+#pragma unroll
+        for (int f = 0; f < NV; ++f) {
+            const int kp = f / DB, db = f % DB;
+            const v4u a = *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
+            o[0][db] = mfma16(a, pb[0][kp], o[0][db]);
+            o[1][db] = mfma16(a, pb[1][kp], o[1][db]);
+        }
     }
 
     if (wave_last_key < 0) return;
