@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
     using Stage = TileStage<D, NT>;
     constexpr int BN = Stage::BN, KROW = Stage::KROW, VROW = Stage::VROW;
     constexpr int KTILE = BN * KROW, VTILE = D * VROW;
-    constexpr int kWin = 8;              // fragment prefetch distance (register quads)
+    constexpr int kWin = 4;              // fragment prefetch distance (register quads)
     constexpr int NK = 4 * KS;           // K fragments per tile  (key block, k-step)
     constexpr int NV = 2 * DB;           // V^T fragments per tile (key pair, d block)
 
