@@ -31,105 +31,81 @@ __device__ __forceinline__ f32x16 mfma32(v4u a, v4u b, f32x16 c)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
 }
 
-// Position of key (within a 64-key tile) inside a transposed V row in LDS.  The forward kernel
-// contracts 32 keys per P.V MFMA; lane group g = lane/16 holds, for its query, the probabilities
-// of keys 16*kb + 4g + r (r = 0..3) of every 16-key block kb, and feeds blocks 2*kp and 2*kp+1 as
-// the eight B elements of key pair kp.  Key 32*kp + 16*h + 4*g + r therefore sits at
-// 32*kp + 8*g + 4*h + r, so that the matching V^T elements are 16 contiguous bytes.
-__device__ __forceinline__ int vt_pos(int key)
-{
-    return (key & 32) + ((key & 12) << 1) + ((key & 16) >> 2) + (key & 3);
-}
-
 // ------------------------------------------------------------------------------------------
-// Global -> register -> LDS staging of one 64-key K/V tile by a workgroup of NT threads.
-// K rows are copied as they are.  V is transposed: thread (v_dq, v_k0) holds an 8-wide d slice of
-// PIECES consecutive keys and writes, for each of the 8 d rows, PIECES consecutive bf16.
+// Global -> register -> LDS staging of one 64-key K/V tile by a workgroup of NT threads: K and V
+// rows are copied as they are, 16 bytes per thread and piece.  V is NOT transposed on the way in:
+// the V^T operands of O^T = V^T P^T are read with ds_read_b64_tr_b16, the transposing LDS load of
+// gfx950 (see lds_read_tr16 below); two plain 16-byte stores per piece replace the transposing
+// 4-byte stores and their packing VALU work (about 1 % of the kernel time, and 16 VGPRs).
 //
 // LDS layout, measured on gfx950: a ds_read_b128 is served half a wave at a time and is free of
-// bank conflicts when the 32 lanes touch 32 different 16-byte slots modulo 512 bytes.  The
-// fragment reads of the forward kernel have 16-lane row groups (lane%16 = row, lane/16 = 16-byte
-// piece), so a half wave reads 16 rows x 2 adjacent pieces: the row pitch must be an odd multiple
-// of 32 bytes -- 288 bytes for K rows (D = 128), 160 bytes for V^T rows.  With the pitches of the
-// 32-lane layout (272 / 144 bytes) this read pattern showed 3.7x the bank-conflict cycles.
-// Inside a V^T row (64 keys = eight 16-byte chunks + pad) the chunk index is XOR-ed with
-// (row/16)%8: constant over a fragment read, and it spreads the transposing 4-byte writes, which
-// otherwise collide 8- to 16-way, over all banks.
+// bank conflicts when the 32 lanes touch 32 different 16-byte slots modulo 512 bytes.  The K
+// fragment reads have 16-lane row groups (lane%16 = row, lane/16 = 16-byte piece), so a half
+// wave reads 16 rows x 2 adjacent pieces: the row pitch must be an odd multiple of 32 bytes
+// (288 bytes for D = 128; 272 bytes showed 3.7x the bank-conflict cycles).  The transposing V
+// reads touch 16 consecutive rows x 32 bytes per instruction; the same pitch keeps them apart.
 template <int D, int NT>
 struct TileStage {
     static constexpr int BN = 64;
-    static constexpr int KROW = D + 16;
-    static constexpr int VROW = BN + 16;
+    static constexpr int KROW = D + 16;      // row pitch of both tiles, elements
     static constexpr int C8 = D / 8;
     static constexpr int PIECES = BN * C8 / NT;
     static_assert(PIECES == 1 || PIECES == 2 || PIECES == 4, "tile/threads mismatch");
     v4u kpre[PIECES], vpre[PIECES];
-    uint32_t k_goff, v_goff;      // byte offsets of this thread's first piece inside a tile (global)
-    uint32_t k_loff, v_loff;      // element offsets inside an LDS tile
-    int k_row, v_row;             // tile-relative rows of the first piece (for the clamped tail path)
+    uint32_t goff;                // byte offset of this thread's first piece inside a tile (global)
+    uint32_t loff;                // element offset inside an LDS tile
+    int row0;                     // tile-relative row of the first piece (for the clamped tail path)
 
     __device__ __forceinline__ void init(int tid)
     {
-        const int v_dq = tid % C8, v_k0 = (tid / C8) * PIECES;
-        k_row = tid / C8;
-        v_row = v_k0;
-        k_goff = (uint32_t)(k_row * D + (tid % C8) * 8) * 2u;
-        v_goff = (uint32_t)(v_k0 * D + v_dq * 8) * 2u;
-        k_loff = (uint32_t)(k_row * KROW + (tid % C8) * 8);
-        const int pos = vt_pos(v_k0);
-        const int sw = (v_dq >> 1) & 7;
-        v_loff = (uint32_t)(v_dq * 8 * VROW + ((((pos >> 3) ^ sw) << 3) | (pos & 7)));
+        row0 = tid / C8;
+        goff = (uint32_t)(row0 * D + (tid % C8) * 8) * 2u;
+        loff = (uint32_t)(row0 * KROW + (tid % C8) * 8);
     }
-    // Kt, Vt: tile base pointers (uniform); rows_left = n - j0 (>= 1).  Piece i of K sits NT/C8 rows
-    // further down, piece i of V one row further down.
+    // Kt, Vt: tile base pointers (uniform); rows_left = n - j0 (>= 1).  Piece i sits NT/C8 rows
+    // further down.
     __device__ __forceinline__ void load(const u16 *Kt, const u16 *Vt, int rows_left)
     {
         const char *kb = (const char *)Kt, *vb = (const char *)Vt;
         if (rows_left >= BN) {
 #pragma unroll
             for (int i = 0; i < PIECES; ++i) {
-                kpre[i] = *(const v4u *)(kb + (k_goff + (uint32_t)(i * (NT / C8) * D * 2)));
-                vpre[i] = *(const v4u *)(vb + (v_goff + (uint32_t)(i * D * 2)));
+                const uint32_t off = goff + (uint32_t)(i * (NT / C8) * D * 2);
+                kpre[i] = *(const v4u *)(kb + off);
+                vpre[i] = *(const v4u *)(vb + off);
             }
         } else {   // ragged last tile: rows past the end repeat the last valid row
 #pragma unroll
             for (int i = 0; i < PIECES; ++i) {
-                const int kr = k_row + i * (NT / C8), vr = v_row + i;
-                const int kd = kr < rows_left ? 0 : kr - (rows_left - 1);
-                const int vd = vr < rows_left ? 0 : vr - (rows_left - 1);
-                kpre[i] = *(const v4u *)(kb + (k_goff + (uint32_t)((i * (NT / C8) - kd) * D * 2)));
-                vpre[i] = *(const v4u *)(vb + (v_goff + (uint32_t)((i - vd) * D * 2)));
+                const int r = row0 + i * (NT / C8);
+                const int back = r < rows_left ? 0 : r - (rows_left - 1);
+                const uint32_t off = goff + (uint32_t)((i * (NT / C8) - back) * D * 2);
+                kpre[i] = *(const v4u *)(kb + off);
+                vpre[i] = *(const v4u *)(vb + off);
             }
         }
     }
     __device__ __forceinline__ void store(u16 *dk, u16 *dv) const
     {
 #pragma unroll
-        for (int i = 0; i < PIECES; ++i) *(v4u *)(dk + k_loff + i * (NT / C8) * KROW) = kpre[i];
-        u16 *dst0 = dv + v_loff;
-#pragma unroll
-        for (int dd = 0; dd < 8; ++dd) {
-            u16 e[PIECES];
-#pragma unroll
-            for (int i = 0; i < PIECES; ++i) {
-                const uint32_t w = (dd >> 1) == 0 ? vpre[i].x : (dd >> 1) == 1 ? vpre[i].y
-                                   : (dd >> 1) == 2 ? vpre[i].z : vpre[i].w;
-                e[i] = (dd & 1) ? (u16)(w >> 16) : (u16)(w & 0xffffu);
-            }
-            u16 *dst = dst0 + dd * VROW;
-            if constexpr (PIECES == 4) {
-                v2u w2;
-                w2.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
-                w2.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
-                *(v2u *)dst = w2;
-            } else if constexpr (PIECES == 2) {
-                *(uint32_t *)dst = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
-            } else {
-                *dst = e[0];
-            }
+        for (int i = 0; i < PIECES; ++i) {
+            *(v4u *)(dk + loff + i * (NT / C8) * KROW) = kpre[i];
+            *(v4u *)(dv + loff + i * (NT / C8) * KROW) = vpre[i];
         }
     }
 };
+
+// ds_read_b64_tr_b16 (gfx950).  Within each group of 16 lanes, lane r supplies the address of four
+// consecutive 16-bit elements B[r][0..3]; lane i of the group receives, as element j,
+// B[4*j + i/4][i%4] (established by writing element indices into LDS and reading them back).  With
+// lane r = 4*j + q pointing at V[key_j][d0 + 4*q .. +3], lane i therefore receives
+// V[key_0..3][d0 + i]: four keys of one d column, half of an MFMA A operand of V^T.
+__device__ __forceinline__ v2u lds_read_tr16(const u16 *p)
+{
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    const v4s r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s *)p);
+    return __builtin_bit_cast(v2u, r);
+}
 
 __device__ __forceinline__ f32x4 mfma16(v4u a, v4u b, f32x4 c)
 {
@@ -172,7 +148,9 @@ __device__ __forceinline__ float softmax_row(const f32x4 (&s)[4], float c, float
 // the accumulator data per flop.  S^T = K Q^T is formed per 16-key block and 16-query block: a lane
 // owns one query column (lane % 16) of each of the wave's two query blocks and, per key block, the
 // four keys 4*(lane/16)..+3; row statistics are per-lane scalars reduced over lane/16 once at
-// the end, and the probabilities are already the B operand of O^T = V^T P^T (see vt_pos).
+// the end, and the probabilities are already the B operand of O^T = V^T P^T: key pair kp
+// contracts the 32 keys of key blocks 2*kp and 2*kp+1, lane group g = lane/16 supplying keys
+// 4g..4g+3 of each, and the transposing LDS reads fetch exactly those V rows.
 //
 // Wall time follows the energy of the launch (the shader clock falls to about 1.8 GHz under
 // this kernel with random data), so the kernel keeps the instruction count and the data
@@ -189,7 +167,7 @@ constexpr int kFwdWaves = 8;
 template <int D>
 constexpr size_t fwd_lds_bytes()
 {
-    return sizeof(u16) * (size_t)(2 * 64 * (D + 16) + 3 * D * (64 + 16));
+    return sizeof(u16) * (size_t)(5 * 64 * (D + 16));      // two K slots, three V slots
 }
 
 template <int D>
@@ -200,8 +178,8 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
     constexpr int KS = D / 32;           // MFMA k-steps of Q.K^T
     constexpr int DB = D / 16;           // 16-wide output blocks of P.V
     using Stage = TileStage<D, NT>;
-    constexpr int BN = Stage::BN, KROW = Stage::KROW, VROW = Stage::VROW;
-    constexpr int KTILE = BN * KROW, VTILE = D * VROW;
+    constexpr int BN = Stage::BN, KROW = Stage::KROW;
+    constexpr int KTILE = BN * KROW, VTILE = BN * KROW;
     constexpr int kWin = 4;              // fragment prefetch distance (register quads)
     constexpr int NK = 4 * KS;           // K fragments per tile  (key block, k-step)
     constexpr int NV = 2 * DB;           // V^T fragments per tile (key pair, d block)
@@ -259,7 +237,7 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
     const float c = p.scale * kLog2e;
     // per-lane fragment offsets (elements) inside a K tile / V^T tile
     const int k_frag0 = ln * KROW + 8 * lg;
-    const int v_frag0 = ln * VROW;
+    const int v_frag0 = (4 * lg + (ln >> 2)) * KROW + 4 * (ln & 3);   // see lds_read_tr16
 
     Stage st;
     st.init(tid);
@@ -333,9 +311,11 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
             if (t <= tl) {
                 asm volatile("; in-step wave" ::: "memory");
                 const u16 *sv = ldsV + vslot * VTILE + v_frag0;
-                auto vfrag = [&](int i) -> v4u { // i = DB*kp + db: d 16*db + ln, key pair kp;
-                    const int kp = i / DB, db = i % DB;  // chunk XOR-ed with (row/16)%8 = db%8
-                    return *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
+                auto vfrag = [&](int i) -> v4u { // i = DB*kp + db: d 16*db + ln, key pair kp
+                    const int kp = i / DB, db = i % DB;
+                    const v2u lo = lds_read_tr16(sv + (32 * kp) * KROW + 16 * db);        // keys of block 2*kp
+                    const v2u hi = lds_read_tr16(sv + (32 * kp + 16) * KROW + 16 * db);   // and of block 2*kp+1
+                    return (v4u){lo.x, lo.y, hi.x, hi.y};
                 };
                 // ---- S^T = K Q^T; fragments stream through a rolling window of kWin register
                 // quads, each feeding the MFMAs of both query blocks; the window is refilled with
@@ -357,9 +337,14 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
                 }
                 __builtin_amdgcn_sched_group_barrier(0x100, kWin, 0);
 #pragma unroll
-                for (int f = 0; f < NK; ++f) {
+                for (int f = 0; f < NK - kWin; ++f) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+#pragma unroll
+                for (int f = NK - kWin; f < NK; ++f) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // a V^T fragment is two reads
                 }
                 mask_tile(s, j0);
                 softmax_phase(s);
@@ -373,7 +358,7 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 #pragma unroll
                 for (int f = 0; f < NV; ++f) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                    if (f + kWin < NV) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if (f + kWin < NV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                 }
             }
         } else {
@@ -383,7 +368,9 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
                 const u16 *sv = ldsV + (vslot == 0 ? 2 : vslot - 1) * VTILE + v_frag0;   // tile t-1
                 auto vfrag = [&](int i) -> v4u {
                     const int kp = i / DB, db = i % DB;
-                    return *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
+                    const v2u lo = lds_read_tr16(sv + (32 * kp) * KROW + 16 * db);
+                    const v2u hi = lds_read_tr16(sv + (32 * kp + 16) * KROW + 16 * db);
+                    return (v4u){lo.x, lo.y, hi.x, hi.y};
                 };
                 v4u fw[kWin];
                 if (do_pv) {
@@ -398,9 +385,14 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
                         const int g = f + kWin;
                         fw[f % kWin] = g < NV ? vfrag(g) : kfrag(g - NV);
                     }
-                    __builtin_amdgcn_sched_group_barrier(0x100, kWin, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kWin, 0);
 #pragma unroll
-                    for (int f = 0; f < NV; ++f) {
+                    for (int f = 0; f < NV - kWin; ++f) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    }
+#pragma unroll
+                    for (int f = NV - kWin; f < NV; ++f) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     }
@@ -448,7 +440,9 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 #pragma unroll
         for (int f = 0; f < NV; ++f) {
             const int kp = f / DB, db = f % DB;
-            const v4u a = *(const v4u *)(sv + db * 16 * VROW + ((4 * kp + lg) ^ (db & 7)) * 8);
+            const v2u lo = lds_read_tr16(sv + (32 * kp) * KROW + 16 * db);
+            const v2u hi = lds_read_tr16(sv + (32 * kp + 16) * KROW + 16 * db);
+            const v4u a = {lo.x, lo.y, hi.x, hi.y};
             o[0][db] = mfma16(a, pb[0][kp], o[0][db]);
             o[1][db] = mfma16(a, pb[1][kp], o[1][db]);
         }
