@@ -11,8 +11,9 @@
 // Both kernels compute the TRANSPOSED logit tile  S^T = K Q^T: a lane then owns one query column
 // and a few key rows, so the softmax row statistics are per-lane scalars (exchanged across the
 // lane groups once), and the probabilities are already laid out as the B operand of
-// O^T = V^T P^T  once the contraction index is permuted consistently on the V side (V is written
-// into LDS transposed, with that permutation).  The forward kernel uses
+// O^T = V^T P^T  once the contraction index is permuted consistently on the V side (the V^T
+// operands are fetched from a row-major V tile with gfx950's transposing LDS load, in that
+// permuted key order).  The forward kernel uses
 // v_mfma_f32_16x16x32_bf16, the score kernel v_mfma_f32_32x32x16_bf16 (it is bound by VALU issue,
 // where the larger tile's fewer MFMA instructions matter more than its higher energy per flop).
 //
@@ -139,7 +140,7 @@ __device__ __forceinline__ float softmax_row(const f32x4 (&s)[4], float c, float
 
 // Forward: out, lse.  One workgroup = 8 waves; a wave owns 32 chunk rows of one query head.  The
 // waves of a workgroup cover `gp` query heads of one KV group times 8/gp row slabs, so the K/V
-// tiles staged in LDS (double-buffered, one barrier per 64-key tile) serve every wave.
+// tiles staged in LDS (two K slots, three V slots, one barrier per 64-key tile) serve every wave.
 //
 // MFMA shape: v_mfma_f32_16x16x32_bf16 (A[m][k]: lane l holds m = l%16, k = 8*(l/16)..+7; B[k][n]:
 // n = l%16, same k; C[m][n]: n = l%16, m = 4*(l/16) + e).  Measured on gfx950 with random bf16
@@ -152,7 +153,7 @@ __device__ __forceinline__ float softmax_row(const f32x4 (&s)[4], float c, float
 // contracts the 32 keys of key blocks 2*kp and 2*kp+1, lane group g = lane/16 supplying keys
 // 4g..4g+3 of each, and the transposing LDS reads fetch exactly those V rows.
 //
-// Wall time follows the energy of the launch (the shader clock falls to about 1.8 GHz under
+// Wall time follows the energy of the launch (the shader clock falls to about 1.95 GHz under
 // this kernel with random data), so the kernel keeps the instruction count and the data
 // movement per tile small:
 //   - no row maximum on the fast path: probabilities are formed against the current reference
