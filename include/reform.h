@@ -152,7 +152,7 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *desc,
  *     topk_score  [n_query][k] fp32 out (sim of the selected rows), may be NULL
  *     union_idx   [n_ctx] int32 out (first union_count entries), may be NULL (then no union)
  *     union_count one int32 in device memory, out, required iff union_idx != NULL
- * Supported: n_ctx < 2^31; dim % 8 == 0; any n_query >= 1 (processed 16 at a time).
+ * Supported: n_ctx <= 2^31 - 65536; dim % 8 == 0; any n_query >= 1 (processed 16 at a time).
  */
 typedef struct {
     uint32_t struct_size;

@@ -82,7 +82,7 @@ reform_status check_gather(const reform_gather_desc *d)
     if (d->k <= 0 || d->k > d->n_ctx) return REFORM_ERR_INVALID_ARG;
     if (d->radius < 0 || d->n_head_keep < 0 || d->n_tail_keep < 0) return REFORM_ERR_INVALID_ARG;
     if (!(d->eps > 0.f) || !std::isfinite(d->eps)) return REFORM_ERR_INVALID_ARG;
-    if (d->n_ctx >= (1ll << 31)) return REFORM_ERR_UNSUPPORTED;
+    if (d->n_ctx > (1ll << 31) - 65536) return REFORM_ERR_UNSUPPORTED;   // int32 indices, with room for tile overhang
     if (d->dim % 8) return REFORM_ERR_UNSUPPORTED;
     if (d->n_query > 65535) return REFORM_ERR_UNSUPPORTED;
     const int grp = d->n_query < 16 ? d->n_query : 16;

@@ -10,6 +10,8 @@
 //   select_count  final pick, then per workgroup the number of candidates above / equal to the
 //                 threshold key
 //   select_write  ordered emission: everything above the threshold, then the lowest-index ties
+//   select_fused  rows of at most 32768 candidates: all of the above in one launch, one workgroup
+//                 per row, keys held in registers
 // Candidates in the first n_sink or last n_recent slots get the maximal key (always selected).
 #include "common.h"
 
@@ -181,12 +183,169 @@ __global__ __launch_bounds__(256) void select_count(SelParams p)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Building blocks shared by the ordered emission of the multi-launch path and by the
+// single-launch selection of short rows.  A wave owns a contiguous range of NIT * 256
+// candidates starting at w_lo; in step `it` lane l holds the four consecutive candidates
+// w_lo + it * 256 + 4 * l + (0..3).  Every global access of a step is then one contiguous block
+// per wave, and positions in index order follow from wave ballots (no cross-lane data movement)
+// plus the running counts of the wave.  `FULL` marks a wave whose whole range lies inside the row
+// (no per-candidate bounds test).
+__device__ __forceinline__ int lanes_below(unsigned long long m)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// Keys of the wave's range; slots at or beyond N hold 0 and are masked by the users.
+template <int NIT>
+__device__ __forceinline__ void range_keys(const SelParams &p, const float *s, int N, int w_lo, uint32_t (&u)[NIT][4])
+{
+    const int t_lane = w_lo + (threadIdx.x & 63) * 4;
+    const int w_hi = w_lo + NIT * 256;
+    const bool forced = w_lo < p.n_sink || w_hi > N - p.n_recent;     // some slot of the range may be forced in
+    if (w_hi <= N && !forced && sel_rows_aligned(p)) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const float4 v = *(const float4 *)(s + t_lane + it * 256);
+            u[it][0] = ordered_key(v.x);
+            u[it][1] = ordered_key(v.y);
+            u[it][2] = ordered_key(v.z);
+            u[it][3] = ordered_key(v.w);
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int t = t_lane + it * 256 + j;
+                const uint32_t key = sel_key(p, s, min(t, N - 1));
+                u[it][j] = t < N ? key : 0u;
+            }
+    }
+}
+
+// Candidates of the wave's range above / equal to the threshold key (wave-uniform results).
+template <int NIT, bool FULL>
+__device__ __forceinline__ void range_count(const uint32_t (&u)[NIT][4], int N, int w_lo, uint32_t T, int &gt, int &eq)
+{
+    const int t_lane = w_lo + (threadIdx.x & 63) * 4;
+    gt = 0;
+    eq = 0;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool valid = FULL || t_lane + it * 256 + j < N;
+            gt += __popcll(__ballot(valid && u[it][j] > T));
+            eq += __popcll(__ballot(valid && u[it][j] == T));
+        }
+}
+
+// Four consecutive 4-byte entries src[t..t+3] (those at or beyond N come back as 0).
+template <bool FULL>
+__device__ __forceinline__ int4 load_quad(const int32_t *src, bool quads, int t, int N)
+{
+    if (quads && (FULL || t + 4 <= N)) return *(const int4 *)(src + t);
+    int4 r;
+    r.x = t < N ? src[t] : 0;
+    r.y = t + 1 < N ? src[t + 1] : 0;
+    r.z = t + 2 < N ? src[t + 2] : 0;
+    r.w = t + 3 < N ? src[t + 3] : 0;
+    return r;
+}
+
+// Ordered emission of the wave's range: dest_run = selected candidates before the range,
+// eq_run = candidates equal to T before it (both wave-uniform).  The values and the companion
+// entries of a step are fetched as whole quads one step ahead, never per selected candidate
+// (a load feeding a store inside the per-candidate branch costs a memory round trip each).
+template <int NIT, bool FULL>
+__device__ __forceinline__ void range_emit(const SelParams &p, int q, const uint32_t (&u)[NIT][4], int N, int w_lo,
+                                           uint32_t T, int need_eq, int dest_run, int eq_run)
+{
+    const int t_lane = w_lo + (threadIdx.x & 63) * 4;
+    const int32_t *sv = (const int32_t *)(p.vals + (size_t)q * p.ld);
+    int32_t *orank = p.out_rank ? p.out_rank + (size_t)q * p.ld : nullptr;
+    const bool rank_quads = ((p.ld & 3) == 0) && ((((uintptr_t)p.out_rank) & 15) == 0);
+    const bool val_quads = sel_rows_aligned(p);
+    const bool side_quads = ((p.ld & 3) == 0) && ((((uintptr_t)p.side_src) & 15) == 0);
+    int32_t *oi = p.out_idx + (size_t)q * p.out_ld;
+    int32_t *os = p.out_val ? (int32_t *)(p.out_val + (size_t)q * p.out_ld) : nullptr;
+    const int32_t *ss = p.side_src ? p.side_src + (size_t)q * p.ld : nullptr;
+    int32_t *sd = p.side_src ? p.side_dst + (size_t)q * p.out_ld : nullptr;
+    int4 val_nx = make_int4(0, 0, 0, 0), side_nx = make_int4(0, 0, 0, 0);
+    if (os) val_nx = load_quad<FULL>(sv, val_quads, t_lane, N);
+    if (ss) side_nx = load_quad<FULL>(ss, side_quads, t_lane, N);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int t = t_lane + it * 256;
+        const int4 val4 = val_nx, side4 = side_nx;
+        if (it + 1 < NIT) {
+            if (os) val_nx = load_quad<FULL>(sv, val_quads, t + 256, N);
+            if (ss) side_nx = load_quad<FULL>(ss, side_quads, t + 256, N);
+        }
+        const int val[4] = {val4.x, val4.y, val4.z, val4.w};
+        const int side[4] = {side4.x, side4.y, side4.z, side4.w};
+        bool keep[4];
+        unsigned long long me[4];
+        unsigned long long any_eq = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            me[j] = __ballot((FULL || t + j < N) && u[it][j] == T);
+            any_eq |= me[j];
+        }
+        if (any_eq) {                                         // ties inside these 256 candidates: lowest index first
+            int eq_seen = eq_run;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) eq_seen += lanes_below(me[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool is_eq = (FULL || t + j < N) && u[it][j] == T;
+                keep[j] = (FULL || t + j < N) && (u[it][j] > T || (is_eq && eq_seen < need_eq));
+                eq_seen += is_eq;
+                eq_run += __popcll(me[j]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) keep[j] = (FULL || t + j < N) && u[it][j] > T;
+        }
+        int dest = dest_run;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned long long mk = __ballot(keep[j]);
+            dest += lanes_below(mk);
+            dest_run += __popcll(mk);
+        }
+        if (orank) {
+            const int r1 = dest + keep[0], r2 = r1 + keep[1], r3 = r2 + keep[2];
+            if (rank_quads && (FULL || t + 4 <= N)) {
+                *(int4 *)(orank + t) = make_int4(dest, r1, r2, r3);
+            } else {
+                if (t < N) orank[t] = dest;
+                if (t + 1 < N) orank[t + 1] = r1;
+                if (t + 2 < N) orank[t + 2] = r2;
+                if (t + 3 < N) orank[t + 3] = r3;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (keep[j] && dest < p.k) {
+                oi[dest] = (int32_t)(t + j);
+                if (os) os[dest] = val[j];
+                if (ss) sd[dest] = side[j];
+            }
+            dest += keep[j];
+        }
+    }
+}
+
 // grid (nblk, nq): ordered emission of the selected indices (ascending), lowest-index ties.
+// A workgroup covers 4096 candidates, a wave 1024 of them.
 __global__ __launch_bounds__(256) void select_write(SelParams p)
 {
-    __shared__ int tmp[4];
+    __shared__ int wtot[2][4];
     __shared__ int sh_gt, sh_eq;
     const int q = blockIdx.y, tid = threadIdx.x, blk = blockIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const uint32_t T = p.sel_prefix[2 * p.nq + q];
     const int need_eq = p.sel_krem[2 * p.nq + q];
     // candidates above / equal to T in the blocks before this one
@@ -197,65 +356,143 @@ __global__ __launch_bounds__(256) void select_write(SelParams p)
     for (int o = 32; o >= 1; o >>= 1) { gt_b += __shfl_xor(gt_b, o); eq_b += __shfl_xor(eq_b, o); }
     if (tid == 0) { sh_gt = 0; sh_eq = 0; }
     __syncthreads();
-    if ((tid & 63) == 0) { atomicAdd(&sh_gt, gt_b); atomicAdd(&sh_eq, eq_b); }
-    __syncthreads();
-    const int base_gt = sh_gt, base_eq = sh_eq;
+    if (lane == 0) { atomicAdd(&sh_gt, gt_b); atomicAdd(&sh_eq, eq_b); }
 
     const float *s = p.vals + (size_t)q * p.ld;
-    const long t0 = (long)blk * kSelBlock + tid * 16;
-    uint32_t u[16];
-    float val[16];
-    int gt_c = 0, eq_c = 0;
-    if (sel_rows_aligned(p) && t0 + 16 <= p.N) {
+    const int N = (int)p.N;
+    const int w_lo = blk * kSelBlock + wave * 1024;
+    const bool full = w_lo + 1024 <= N;
+    uint32_t u[4][4];
+    range_keys<4>(p, s, N, w_lo, u);
+    int gt_w, eq_w;
+    if (full) range_count<4, true>(u, N, w_lo, T, gt_w, eq_w);
+    else range_count<4, false>(u, N, w_lo, T, gt_w, eq_w);
+    if (lane == 0) { wtot[0][wave] = gt_w; wtot[1][wave] = eq_w; }
+    __syncthreads();
+    int base_gt = sh_gt, base_eq = sh_eq;                         // above / equal to T before this wave's range
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+        if (w < wave) { base_gt += wtot[0][w]; base_eq += wtot[1][w]; }
+    const int dest_run = base_gt + min(base_eq, need_eq);
+    if (full) range_emit<4, true>(p, q, u, N, w_lo, T, need_eq, dest_run, base_eq);
+    else range_emit<4, false>(p, q, u, N, w_lo, T, need_eq, dest_run, base_eq);
+}
+
+// ------------------------------------------------------------------------------------------
+// Rows of at most 32768 candidates: the whole selection of a row in ONE launch by one workgroup
+// of 1024 threads (16 waves, each owning NIT * 256 candidates).  The row is read once; its keys
+// stay in registers through the three radix passes (LDS histogram, pick by a workgroup scan) and
+// the ordered emission.  Results are identical to the multi-launch path; the per-pass selection
+// state is not written back.  One compute unit does all the work of a row, so beyond this size
+// the multi-launch path, which spreads a row over many, is faster.
+constexpr int kFusedMaxN = 32768;
+
+// Histogram of digit PASS over the keys a thread holds (candidates matching the prefix only).
+template <int NIT, int PASS, bool FULL>
+__device__ __forceinline__ void fused_hist(const uint32_t (&u)[NIT][4], int N, int w_lo, uint32_t prefix, int *h)
+{
+    const int lane = threadIdx.x & 63;
+    const int t_lane = w_lo + lane * 4;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int t = t_lane + it * 256;
+        bool m[4];
+        bool same = true;                                     // all four count and share one digit
+        const int d0 = digit_of(u[it][0], PASS);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float4 v = *(const float4 *)(s + t0 + 4 * j);
-            val[4 * j] = v.x; val[4 * j + 1] = v.y; val[4 * j + 2] = v.z; val[4 * j + 3] = v.w;
+            m[j] = (FULL || t + j < N) && prefix_match(u[it][j], prefix, PASS);
+            same = same && m[j] && digit_of(u[it][j], PASS) == d0;
         }
+        // a wave whose 256 candidates all fall into one bin adds them at once (constant or
+        // narrowly spread rows would otherwise serialise 64 lanes on one LDS address)
+        const int dref = __builtin_amdgcn_readfirstlane(d0);
+        if (__all(same && d0 == dref)) {
+            if (lane == 0) atomicAdd(&h[dref], 256);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            u[i] = sel_key_of(p, val[i], t0 + i);
-            gt_c += u[i] > T;
-            eq_c += u[i] == T;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const long t = t0 + i;
-            const bool valid = t < p.N;
-            val[i] = valid ? s[t] : 0.f;
-            u[i] = valid ? sel_key(p, s, t) : 0u;
-            gt_c += valid && u[i] > T;
-            eq_c += valid && u[i] == T;
-        }
-    }
-    int tot;
-    const int eq_before = base_eq + block256_excl_scan(eq_c, tmp, tot);
-    const int eq_take = max(0, min(eq_c, need_eq - eq_before));
-    const int kept_before_blk = base_gt + min(base_eq, need_eq);
-    int dest = kept_before_blk + block256_excl_scan(gt_c + eq_take, tmp, tot);
-    int eq_seen = eq_before;
-    int32_t *orank = p.out_rank ? p.out_rank + (size_t)q * p.ld : nullptr;
-    int32_t *oi = p.out_idx + (size_t)q * p.out_ld;
-    float *os = p.out_val ? p.out_val + (size_t)q * p.out_ld : nullptr;
-    const int32_t *ss = p.side_src ? p.side_src + (size_t)q * p.ld : nullptr;
-    int32_t *sd = p.side_src ? p.side_dst + (size_t)q * p.out_ld : nullptr;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const long t = t0 + i;
-        if (t >= p.N) break;
-        if (orank) orank[t] = dest;
-        bool keep = u[i] > T;
-        if (u[i] == T) { keep = eq_seen < need_eq; ++eq_seen; }
-        if (keep && dest < p.k) {
-            oi[dest] = (int32_t)t;
-            if (os) os[dest] = val[i];
-            if (ss) sd[dest] = ss[t];
-            ++dest;
+            for (int j = 0; j < 4; ++j)
+                if (m[j]) atomicAdd(&h[digit_of(u[it][j], PASS)], 1);
         }
     }
 }
 
+// Executed by all 1024 threads: pick the digit of the histogram that holds the krem-th largest
+// key (thread t owns digits 2t and 2t+1) and extend the prefix by it.
+template <int PASS>
+__device__ __forceinline__ void fused_pick(uint32_t &prefix, int &krem, const int *h, int *wtot, int *sel)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l0 = h[2 * tid], l1 = h[2 * tid + 1], sum = l0 + l1;
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(incl, o);
+        if (lane >= o) incl += y;
+    }
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    int below = incl - sum, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const int x = wtot[w];
+        if (w < wave) below += x;
+        total += x;
+    }
+    const int above = total - below - sum;                    // candidates with a digit above 2t+1
+    if (above < krem && krem <= above + l1) { sel[0] = 2 * tid + 1; sel[1] = krem - above; }
+    else if (above + l1 < krem && krem <= above + sum) { sel[0] = 2 * tid; sel[1] = krem - above - l1; }
+    __syncthreads();
+    prefix = (prefix << (PASS == 2 ? 10 : 11)) | (uint32_t)sel[0];
+    krem = sel[1];
+    __syncthreads();
+}
+
+template <int NIT>
+__global__ __launch_bounds__(1024) void select_fused(SelParams p)
+{
+    __shared__ int h[2048];
+    __shared__ int wtot[2][16];
+    __shared__ int sel[2];
+    const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (long i = (long)q * 1024 + tid; i < p.zero_extra_n; i += (long)gridDim.x * 1024) p.zero_extra[i] = 0;
+
+    const float *s = p.vals + (size_t)q * p.ld;
+    const int N = (int)p.N;
+    const int w_lo = wave * (NIT * 256);
+    const bool full = w_lo + NIT * 256 <= N;
+    uint32_t u[NIT][4];
+    range_keys<NIT>(p, s, N, w_lo, u);
+
+    uint32_t prefix = 0u;
+    int krem = p.k;
+#define RF_FUSED_PASS(PASS)                                                           \
+    for (int i = tid; i < 2048; i += 1024) h[i] = 0;                                  \
+    __syncthreads();                                                                  \
+    if (full) fused_hist<NIT, PASS, true>(u, N, w_lo, prefix, h);                     \
+    else fused_hist<NIT, PASS, false>(u, N, w_lo, prefix, h);                         \
+    __syncthreads();                                                                  \
+    fused_pick<PASS>(prefix, krem, h, wtot[0], sel);
+    RF_FUSED_PASS(0)
+    RF_FUSED_PASS(1)
+    RF_FUSED_PASS(2)
+#undef RF_FUSED_PASS
+    const uint32_t T = prefix;                                    // key of the k-th largest candidate
+    const int need_eq = krem;                                     // how many candidates equal to it are taken
+
+    int gt_w, eq_w;
+    if (full) range_count<NIT, true>(u, N, w_lo, T, gt_w, eq_w);
+    else range_count<NIT, false>(u, N, w_lo, T, gt_w, eq_w);
+    if (lane == 0) { wtot[0][wave] = gt_w; wtot[1][wave] = eq_w; }
+    __syncthreads();
+    int base_gt = 0, base_eq = 0;                                 // above / equal to T in the waves before this one
+#pragma unroll
+    for (int w = 0; w < 16; ++w)
+        if (w < wave) { base_gt += wtot[0][w]; base_eq += wtot[1][w]; }
+    const int dest_run = base_gt + min(base_eq, need_eq);
+    if (full) range_emit<NIT, true>(p, q, u, N, w_lo, T, need_eq, dest_run, base_eq);
+    else range_emit<NIT, false>(p, q, u, N, w_lo, T, need_eq, dest_run, base_eq);
+}
 
 #define RF_CHECK_LAUNCH()                     \
     do {                                      \
@@ -265,6 +502,14 @@ __global__ __launch_bounds__(256) void select_write(SelParams p)
 
 hipError_t select_topk(const SelParams &p, hipStream_t st)
 {
+    if (p.N <= kFusedMaxN) {
+        if (p.N <= 4096) hipLaunchKernelGGL(select_fused<1>, dim3(p.nq), dim3(1024), 0, st, p);
+        else if (p.N <= 8192) hipLaunchKernelGGL(select_fused<2>, dim3(p.nq), dim3(1024), 0, st, p);
+        else if (p.N <= 16384) hipLaunchKernelGGL(select_fused<4>, dim3(p.nq), dim3(1024), 0, st, p);
+        else hipLaunchKernelGGL(select_fused<8>, dim3(p.nq), dim3(1024), 0, st, p);
+        RF_CHECK_LAUNCH();
+        return hipSuccess;
+    }
     const long nz = max((long)p.nq * 3 * 2048, (long)p.zero_extra_n);
     hipLaunchKernelGGL(sel_zero, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, p);
     RF_CHECK_LAUNCH();

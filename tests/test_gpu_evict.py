@@ -63,6 +63,35 @@ def test_matches_oracle(Hkv, d, n, B, dtype, ties):
     run_case(Hkv, d, n, B, cap, dtype, rand_scores(Hkv, cap, n + B, ties), seed=n)
 
 
+@pytest.mark.parametrize("Hkv,n,B,pad,ties,sink,recent", [
+    (2, 4096, 2000, 0, True, 0, 0),         # one step per lane, aligned rows
+    (2, 4097, 4000, 3, True, 5, 9),         # first size of the four-step variant, unaligned pitch
+    (2, 16384, 8000, 0, False, 0, 0),
+    (1, 16385, 100, 2, True, 0, 3),         # first size of the sixteen-step variant
+    (2, 65535, 32768, 1, True, 0, 0),       # ragged last quad at the largest single-launch size
+    (1, 65536, 65535, 0, True, 0, 0),       # evict exactly one of 65536
+    (2, 65536, 30000, 0, True, 256, 256),
+    (2, 65537, 30000, 3, True, 0, 0),       # first size of the multi-launch selection
+    (2, 70001, 30000, 3, True, 256, 256),
+    (1, 131072, 1000, 0, False, 0, 0),
+])
+def test_selection_paths(Hkv, n, B, pad, ties, sink, recent):
+    """Sizes on both sides of every switch inside the selection (registers per lane, one launch
+    against several), with ties, forced slots and rows that cannot be read as aligned quads."""
+    cap = n + pad
+    run_case(Hkv, 64, n, B, cap, torch.bfloat16, rand_scores(Hkv, cap, n + B + pad, ties), sink, recent, seed=n)
+
+
+def test_constant_and_two_valued_scores_at_full_size():
+    """Every candidate in one histogram bin (the whole-wave shortcut of the single-launch selection)."""
+    kept = run_case(2, 64, 65536, 32768, 65536, torch.bfloat16, torch.full((2, 65536), 0.37))
+    assert (kept == np.arange(32768)).all()
+    s = torch.full((2, 65536), 1.0)
+    s[:, 40000:] = 1.0000001
+    kept = run_case(2, 64, 65536, 32768, 65536, torch.bfloat16, s)
+    assert (kept[:, :7232] == np.arange(7232)).all() and (kept[:, 7232:] == np.arange(40000, 65536)).all()
+
+
 def test_all_scores_equal_keeps_the_first_B():
     kept = run_case(2, 64, 3000, 1200, 3000, torch.bfloat16, torch.ones((2, 3000)))
     assert (kept == np.arange(1200)).all()
