@@ -32,6 +32,8 @@ struct AttnParams {
     int n_row_blocks;
 };
 
+constexpr int kUnionWordsPerBlock = 256;   // bitmap words per workgroup of the union kernels
+
 // Top-k selection problem: nq rows of N candidates (row stride ld), k winners per row.
 struct SelParams {
     const float *vals;

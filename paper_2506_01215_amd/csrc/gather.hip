@@ -17,7 +17,6 @@ namespace reform {
 hipError_t select_topk(const SelParams &p, hipStream_t st);
 
 
-constexpr int kUnionWordsPerBlock = 1024;
 
 // ------------------------------------------------------------------------------------------
 // 16x16x32 operand layout (wave64): A[m][k]: lane l holds m = l%16, k = 8*(l/16)..+7;
@@ -206,12 +205,6 @@ __global__ __launch_bounds__(256) void sim_generic(GatherParams p)
 
 // ------------------------------------------------------------------------------------------
 // Zero the bitmap of one call.
-__global__ void gather_zero(GatherParams p)
-{
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < p.nwords) p.bitmap[i] = 0u;
-}
-
 // ------------------------------------------------------------------------------------------
 // Union with dilation through a bitmap of N bits.
 __device__ __forceinline__ void set_bits(uint32_t *bm, long lo, long hi)   // inclusive range
@@ -245,15 +238,13 @@ __global__ __launch_bounds__(256) void union_mark(GatherParams p)
     }
 }
 
+// One bitmap word per thread, kUnionWordsPerBlock = 256 words (8192 rows) per workgroup.
 __global__ __launch_bounds__(256) void union_count_words(GatherParams p)
 {
     __shared__ int red[4];
     const int tid = threadIdx.x;
-    int c = 0;
-    for (int i = 0; i < kUnionWordsPerBlock / 256; ++i) {
-        const long w = (long)blockIdx.x * kUnionWordsPerBlock + tid * (kUnionWordsPerBlock / 256) + i;
-        if (w < p.nwords) c += __popc(p.bitmap[w]);
-    }
+    const long w = (long)blockIdx.x * kUnionWordsPerBlock + tid;
+    int c = w < p.nwords ? __popc(p.bitmap[w]) : 0;
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
     if ((tid & 63) == 0) red[tid >> 6] = c;
@@ -261,8 +252,11 @@ __global__ __launch_bounds__(256) void union_count_words(GatherParams p)
     if (tid == 0) p.word_cnt[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
+// The set bits of the workgroup's words are expanded into an LDS staging array in ascending
+// order and copied out as one contiguous, coalesced block of indices.
 __global__ __launch_bounds__(256) void union_emit(GatherParams p)
 {
+    __shared__ int32_t stage[kUnionWordsPerBlock * 32];
     __shared__ int tmp[4];
     __shared__ int sh_base;
     const int tid = threadIdx.x, blk = blockIdx.x;
@@ -273,28 +267,19 @@ __global__ __launch_bounds__(256) void union_emit(GatherParams p)
     if (tid == 0) sh_base = 0;
     __syncthreads();
     if ((tid & 63) == 0) atomicAdd(&sh_base, before);
-    __syncthreads();
-    constexpr int WPT = kUnionWordsPerBlock / 256;
-    uint32_t w[WPT];
-    int c = 0;
-    const long w0 = (long)blk * kUnionWordsPerBlock + tid * WPT;
-#pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-        w[i] = (w0 + i < p.nwords) ? p.bitmap[w0 + i] : 0u;
-        c += __popc(w[i]);
-    }
+    const long w = (long)blk * kUnionWordsPerBlock + tid;
+    uint32_t m = w < p.nwords ? p.bitmap[w] : 0u;
     int tot;
-    int dest = sh_base + block256_excl_scan(c, tmp, tot);
-#pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-        uint32_t m = w[i];
-        while (m) {
-            const int b = __ffs(m) - 1;
-            m &= m - 1;
-            p.union_idx[dest++] = (int32_t)(((w0 + i) << 5) + b);
-        }
+    int pos = block256_excl_scan(__popc(m), tmp, tot);          // synchronises: sh_base is complete after it
+    const int32_t first = (int32_t)(w << 5);
+    while (m) {
+        stage[pos++] = first + (__ffs(m) - 1);
+        m &= m - 1;
     }
-    if (blk == gridDim.x - 1 && tid == 255) *p.union_count = dest;
+    __syncthreads();
+    const int base = sh_base;
+    for (int i = tid; i < tot; i += 256) p.union_idx[base + i] = stage[i];
+    if (blk == gridDim.x - 1 && tid == 0) *p.union_count = base + tot;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -349,11 +334,13 @@ hipError_t gather_similarity(GatherParams p, int dtype_is_bf16, hipStream_t st)
 
 hipError_t gather_select_union(GatherParams p, hipStream_t st)
 {
+    if (p.union_idx) {                        // the selection's clearing launch also clears the bitmap
+        p.sel.zero_extra = (int *)p.bitmap;
+        p.sel.zero_extra_n = p.nwords;
+    }
     hipError_t es = select_topk(p.sel, st);
     if (es != hipSuccess) return es;
     if (p.union_idx) {
-        hipLaunchKernelGGL(gather_zero, dim3((unsigned)((p.nwords + 255) / 256)), dim3(256), 0, st, p);
-        RF_CHECK_LAUNCH();
         const long total = max((long)p.nq * p.k, (long)p.nwords);
         hipLaunchKernelGGL(union_mark, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
         RF_CHECK_LAUNCH();

@@ -107,7 +107,7 @@ GatherLayout gather_layout(const reform_gather_desc *d)
     GatherLayout L;
     L.nblk = (int)((d->n_ctx + 4095) / 4096);
     L.nwords = (int)((d->n_ctx + 31) / 32);
-    L.nublk = (L.nwords + 1023) / 1024;
+    L.nublk = (L.nwords + kUnionWordsPerBlock - 1) / kUnionWordsPerBlock;
     size_t off = 0;
     L.sim = off;    off += align_up((size_t)d->n_query * sim_pitch(d->n_ctx) * sizeof(float));
     L.hist = off;   off += align_up((size_t)d->n_query * 3 * 2048 * sizeof(int));

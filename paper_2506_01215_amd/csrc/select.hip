@@ -18,6 +18,7 @@
 namespace reform {
 
 constexpr int kSelBlock = 4096;      // candidates per selection workgroup (256 threads x 16)
+constexpr int kHistWorkgroups = 2048; // the histogram passes use about this many workgroups at most
 
 __device__ __forceinline__ uint32_t sel_key(const SelParams &p, const float *row, long t)
 {
@@ -84,7 +85,7 @@ __device__ __forceinline__ void select_pick(const SelParams &p, int q, int pass,
     __syncthreads();
 }
 
-// grid (nblk, nq): histogram of the current digit over the candidates matching the prefix.
+// grid (<= nblk, nq): histogram of the current digit over the candidates matching the prefix.
 __global__ __launch_bounds__(256) void select_hist(SelParams p, int pass)
 {
     __shared__ int h[2048];
@@ -103,26 +104,30 @@ __global__ __launch_bounds__(256) void select_hist(SelParams p, int pass)
     }
     __syncthreads();
     const float *s = p.vals + (size_t)q * p.ld;
-    const long t0 = (long)blockIdx.x * kSelBlock;
-    if (sel_rows_aligned(p) && t0 + kSelBlock <= p.N) {
-        // full, aligned block: 16-byte loads, four candidates per lane and step
+    // a workgroup takes every gridDim.x-th block of 4096 candidates (long rows: fewer, longer
+    // workgroups, so the pick above and the merge below are paid less often)
+    for (int blk = blockIdx.x; blk < p.nblk; blk += gridDim.x) {
+        const long t0 = (long)blk * kSelBlock;
+        if (sel_rows_aligned(p) && t0 + kSelBlock <= p.N) {
+            // full, aligned block: 16-byte loads, four candidates per lane and step
 #pragma unroll
-        for (int it = 0; it < kSelBlock / 1024; ++it) {
-            const long t = t0 + (it * 256 + tid) * 4;
-            const float4 v = *(const float4 *)(s + t);
-            const float x[4] = {v.x, v.y, v.z, v.w};
+            for (int it = 0; it < kSelBlock / 1024; ++it) {
+                const long t = t0 + (it * 256 + tid) * 4;
+                const float4 v = *(const float4 *)(s + t);
+                const float x[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t u = sel_key_of(p, x[j], t + j);
-                if (prefix_match(u, prefix, pass)) atomicAdd(&h[digit_of(u, pass)], 1);
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t u = sel_key_of(p, x[j], t + j);
+                    if (prefix_match(u, prefix, pass)) atomicAdd(&h[digit_of(u, pass)], 1);
+                }
             }
-        }
-    } else {
-        for (int i = tid; i < kSelBlock; i += 256) {
-            const long t = t0 + i;
-            if (t < p.N) {
-                const uint32_t u = sel_key(p, s, t);
-                if (prefix_match(u, prefix, pass)) atomicAdd(&h[digit_of(u, pass)], 1);
+        } else {
+            for (int i = tid; i < kSelBlock; i += 256) {
+                const long t = t0 + i;
+                if (t < p.N) {
+                    const uint32_t u = sel_key(p, s, t);
+                    if (prefix_match(u, prefix, pass)) atomicAdd(&h[digit_of(u, pass)], 1);
+                }
             }
         }
     }
@@ -514,8 +519,10 @@ hipError_t select_topk(const SelParams &p, hipStream_t st)
     hipLaunchKernelGGL(sel_zero, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, p);
     RF_CHECK_LAUNCH();
     const dim3 sgrid(p.nblk, p.nq);
+    const int hblk = max(1, kHistWorkgroups / p.nq);       // workgroups per row of the histogram passes
+    const dim3 hgrid(min(p.nblk, hblk), p.nq);
     for (int pass = 0; pass < 3; ++pass) {
-        hipLaunchKernelGGL(select_hist, sgrid, dim3(256), 0, st, p, pass);
+        hipLaunchKernelGGL(select_hist, hgrid, dim3(256), 0, st, p, pass);
         RF_CHECK_LAUNCH();
     }
     hipLaunchKernelGGL(select_count, sgrid, dim3(256), 0, st, p);
