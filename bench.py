@@ -283,13 +283,13 @@ def main():
             torch.cuda.synchronize()
             if r >= 2:
                 pool_times.append(a.elapsed_time(b))
-        # embedding construction for one chunk: 16 selected heads x C tokens, normalised into the store
+        # embedding construction for one chunk: 4 layers x 4 selected heads x C tokens, normalised into the store
         emb_times = []
         for r in range(5):
             a, b = ev(), ev()
             a.record()
-            for seg in range(16):
-                binding.reform_embed_save_selected(out[seg], emb, 0, seg * d)
+            for layer in range(4):                    # one call per selected layer: its 4 heads
+                binding.reform_embed_save_selected(out[4 * layer:4 * layer + 4], emb, 0, 4 * layer * d)
             b.record()
             torch.cuda.synchronize()
             if r >= 2:

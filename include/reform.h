@@ -215,22 +215,24 @@ reform_status reform_gather_pooled(const reform_pooled_desc *desc,
                                    void *hip_stream);
 
 /* ------------------------------------------------------------------------------------------- */
-/* reform_embed_save_selected -- Alg. 1 `emb.SaveSelected(qkv)`, one selected head
+/* reform_embed_save_selected -- Alg. 1 `emb.SaveSelected(qkv)`, the selected heads of one tensor
  *
  *     emb[t][col + c] = x_t[c] / max(||x_t||, eps),  c in [0, head_dim)       (Sec. 3.2, the
  *     e_comb equation: the context embedding of a token is the concatenation of the
- *     L2-normalised Q/K/V states of the selected heads; one call writes one such segment for
- *     the n_rows tokens of a chunk)
+ *     L2-normalised Q/K/V states of the selected heads; one call writes n_heads adjacent
+ *     segments for the n_rows tokens of a chunk: head h is read src_head_stride elements after
+ *     head h-1 and written to columns [emb_col + h*head_dim, emb_col + (h+1)*head_dim))
  *
- *     src   the selected head's state of the chunk's first token; token t's vector starts
+ *     src   the first selected head's state of the chunk's first token; token t's vector starts
  *           src_row_stride elements further on for each t (so a [heads][rows][d] or a
  *           [rows][heads][d] tensor can be addressed in place); dtype
  *     emb   embedding row of the chunk's first token in the [n_ctx][emb_dim] store
- *           (emb_row_stride = emb_dim elements); dtype; only columns [emb_col, emb_col+head_dim)
- *           of the n_rows rows are written; with n_rows = 0 nothing is read or written and
- *           both pointers may be NULL
+ *           (emb_row_stride = emb_dim elements); dtype; only columns
+ *           [emb_col, emb_col + n_heads*head_dim) of the n_rows rows are written; with
+ *           n_rows = 0 nothing is read or written and both pointers may be NULL
  * Supported: head_dim * sizeof(dtype) a multiple of 16 and at most 1024 bytes; strides and
- * emb_col multiples of 16 bytes; src and emb 16-byte aligned.  Sums in fp32.
+ * emb_col multiples of 16 bytes; src and emb 16-byte aligned; 1 <= n_heads <= 65535.  Sums in
+ * fp32.
  */
 typedef struct {
     uint32_t struct_size;
@@ -240,6 +242,8 @@ typedef struct {
     int32_t  emb_col;
     int64_t  src_row_stride, emb_row_stride; /* in elements                                    */
     float    eps;                            /* > 0; 1e-12 in the tests                        */
+    int32_t  n_heads;                        /* heads written by this call (adjacent columns)  */
+    int64_t  src_head_stride;                /* in elements; ignored when n_heads == 1         */
 } reform_embed_desc;
 
 reform_status reform_embed_save_selected(const reform_embed_desc *desc,

@@ -74,7 +74,7 @@ class EmbedDesc(ctypes.Structure):
                 ("n_rows", ctypes.c_int64),
                 ("head_dim", ctypes.c_int32), ("emb_col", ctypes.c_int32),
                 ("src_row_stride", ctypes.c_int64), ("emb_row_stride", ctypes.c_int64),
-                ("eps", ctypes.c_float)]
+                ("eps", ctypes.c_float), ("n_heads", ctypes.c_int32), ("src_head_stride", ctypes.c_int64)]
 
 
 class RowsDesc(ctypes.Structure):
@@ -275,14 +275,17 @@ def reform_gather_similarity(emb, qry, eps=1e-8, sim=None, stream=None):
 
 
 def reform_embed_save_selected(src, emb, row0, col, eps=1e-12, stream=None):
-    """src [n_rows, d] (a view of one head's Q, K or V states; any row stride); writes the
-    normalised rows into emb[row0 : row0 + n_rows, col : col + d]."""
+    """src [n_rows, d] (a view of one head's Q, K or V states; any row stride) or
+    [n_heads, n_rows, d] (several heads of one tensor; any head and row strides); writes the
+    normalised rows into emb[row0 : row0 + n_rows, col : col + n_heads * d]."""
     lib = load_library()
-    n, d = src.shape
-    assert src.stride(1) == 1 and emb.is_contiguous() and emb.dtype == src.dtype
+    if src.dim() == 2:
+        src = src.unsqueeze(0)
+    nh, n, d = src.shape
+    assert nh >= 1 and src.stride(2) == 1 and emb.is_contiguous() and emb.dtype == src.dtype
     assert 0 <= row0 and row0 + n <= emb.shape[0]
-    desc = EmbedDesc(ctypes.sizeof(EmbedDesc), _dtype_code(src), n, d, int(col), src.stride(0),
-                     emb.shape[1], float(eps))
+    desc = EmbedDesc(ctypes.sizeof(EmbedDesc), _dtype_code(src), n, d, int(col), src.stride(1),
+                     emb.shape[1], float(eps), nh, src.stride(0) if nh > 1 else 0)
     dst = emb[row0:] if n else emb
     rc = lib.reform_embed_save_selected(ctypes.byref(desc), _ptr(src), _ptr(dst), _stream(stream))
     _check(rc, "reform_embed_save_selected")

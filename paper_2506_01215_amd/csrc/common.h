@@ -93,6 +93,8 @@ struct EmbedParams {
     void *emb;           // embedding row of the first token
     long n_rows;
     long src_stride_bytes, emb_stride_bytes, col_bytes;
+    long src_head_bytes, head_bytes;   // per head (blockIdx.y): source offset, column offset
+    int n_heads;
     int pieces, group;   // 16-byte pieces per head vector; lanes per row (power of two >= pieces, <= 64)
     float eps;
 };

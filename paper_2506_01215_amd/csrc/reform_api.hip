@@ -425,8 +425,11 @@ reform_status reform_embed_save_selected(const reform_embed_desc *d, const void 
     if (!d || d->struct_size != sizeof(reform_embed_desc)) return REFORM_ERR_INVALID_ARG;
     if (d->dtype != REFORM_F32 && d->dtype != REFORM_BF16) return REFORM_ERR_INVALID_ARG;
     if (d->n_rows < 0 || d->head_dim <= 0 || d->emb_col < 0) return REFORM_ERR_INVALID_ARG;
-    if (d->src_row_stride < d->head_dim || d->emb_row_stride < (int64_t)d->emb_col + d->head_dim)
+    if (d->n_heads < 1 || (d->n_heads > 1 && d->src_head_stride < 0)) return REFORM_ERR_INVALID_ARG;
+    if (d->src_row_stride < d->head_dim ||
+        d->emb_row_stride < (int64_t)d->emb_col + (int64_t)d->n_heads * d->head_dim)
         return REFORM_ERR_INVALID_ARG;
+    if (d->n_heads > 65535) return REFORM_ERR_UNSUPPORTED;
     if (!(d->eps > 0.f) || !std::isfinite(d->eps)) return REFORM_ERR_INVALID_ARG;
     if (d->n_rows > 0 && (!src || !emb)) return REFORM_ERR_INVALID_ARG;
     const size_t es = elt_size(d->dtype);
@@ -435,12 +438,16 @@ reform_status reform_embed_save_selected(const reform_embed_desc *d, const void 
     if (((size_t)d->src_row_stride * es) % 16 || ((size_t)d->emb_row_stride * es) % 16 ||
         ((size_t)d->emb_col * es) % 16 || !aligned16(src) || !aligned16(emb))
         return REFORM_ERR_UNSUPPORTED;
+    if (d->n_heads > 1 && ((size_t)d->src_head_stride * es) % 16) return REFORM_ERR_UNSUPPORTED;
     EmbedParams p;
     std::memset(&p, 0, sizeof(p));
     p.src = src; p.emb = emb; p.n_rows = d->n_rows;
     p.src_stride_bytes = (long)(d->src_row_stride * es);
     p.emb_stride_bytes = (long)(d->emb_row_stride * es);
     p.col_bytes = (long)(d->emb_col * es);
+    p.n_heads = d->n_heads;
+    p.src_head_bytes = d->n_heads > 1 ? (long)(d->src_head_stride * es) : 0;
+    p.head_bytes = (long)row_bytes;
     p.pieces = (int)(row_bytes / 16);
     p.group = 1;
     while (p.group < p.pieces) p.group *= 2;

@@ -134,7 +134,8 @@ def test_embed_save_rejects_bad_arguments():
     lib = binding.load_library()
     mk = lambda **kw: binding.EmbedDesc(**{**dict(struct_size=ctypes.sizeof(binding.EmbedDesc), dtype=1,
                                                   n_rows=100, head_dim=128, emb_col=256,
-                                                  src_row_stride=128, emb_row_stride=2048, eps=1e-12),
+                                                  src_row_stride=128, emb_row_stride=2048, eps=1e-12,
+                                                  n_heads=1, src_head_stride=0),
                                            **kw})
     fake = ctypes.c_void_p(0x1000)
     call = lambda d, s=fake, e=fake: lib.reform_embed_save_selected(ctypes.byref(d), s, e, None)
@@ -142,6 +143,10 @@ def test_embed_save_rejects_bad_arguments():
     assert call(mk(dtype=3)) == 1
     assert call(mk(n_rows=-1)) == 1
     assert call(mk(emb_col=2000)) == 1                    # the segment would overrun the row
+    assert call(mk(n_heads=0)) == 1
+    assert call(mk(n_heads=15, src_head_stride=12800)) == 1    # 256 + 15 * 128 columns > 2048
+    assert call(mk(n_heads=2, src_head_stride=-128)) == 1
+    assert call(mk(n_heads=2, src_head_stride=12804)) == 2     # misaligned head stride
     assert call(mk(src_row_stride=64)) == 1               # rows overlap
     assert call(mk(eps=0.0)) == 1
     assert call(mk(), None) == 1

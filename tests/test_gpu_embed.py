@@ -71,6 +71,30 @@ def test_strided_source_rows_and_untouched_columns():
     assert np.all(got[:, :2 * d] == 2.0) and np.all(got[:, 3 * d:] == 2.0)
 
 
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_several_heads_in_one_call(dtype, d):
+    """Heads 1..4 of a [heads][rows][d] tensor (and of a [rows][heads][d] one) written as four
+    adjacent segments by a single call; identical to four one-head calls and to the oracle."""
+    g = torch.Generator().manual_seed(11)
+    n, H = 777, 6
+    x = (torch.randn((H, n, d), generator=g) * 2.0).to(dtype)
+    xd = x.to(DEV)
+    emb = torch.full((n, 6 * d), 3.0, dtype=dtype, device=DEV)
+    binding.reform_embed_save_selected(xd[1:5], emb, 0, d)
+    xt = xd.transpose(0, 1).contiguous()                      # [rows][heads][d]
+    emb_t = torch.full((n, 6 * d), 3.0, dtype=dtype, device=DEV)
+    binding.reform_embed_save_selected(xt.transpose(0, 1)[1:5], emb_t, 0, d)
+    emb_1 = torch.full((n, 6 * d), 3.0, dtype=dtype, device=DEV)
+    for h in range(1, 5):
+        binding.reform_embed_save_selected(xd[h], emb_1, 0, h * d)
+    torch.cuda.synchronize()
+    ref = np.full((n, 6 * d), 3.0)
+    for h in range(1, 5):
+        oracle.embed_segment(to_np(x[h]), ref, h * d)
+    assert_close(to_np(emb), ref, RTOL[dtype], "four heads, one call")
+    assert torch.equal(emb, emb_1) and torch.equal(emb_t, emb_1)
+
+
 def test_store_feeds_the_gather():
     """Embedding store built on the GPU from 4 layers x 4 heads of synthetic Q/K states, then the
     paper's selection on it; the oracle builds its own store in fp64 and selects from that."""
