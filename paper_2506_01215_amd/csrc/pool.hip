@@ -29,14 +29,30 @@ __global__ __launch_bounds__(256) void pool_qmax_window(PoolParams p)
     const int h = (p.window - 1) >> 1;
     const int tile = (int)min((long)kPoolTile, p.N - t0);
     const int span = tile + p.window - 1;            // local slot i <-> token t0 - h + i
-    for (int i = tid; i < span; i += 256) {
+    // max over the query rows: four tokens per lane with 16-byte loads where the rows allow it,
+    // the loads of several rows in flight at once (this pass reads all of sim: it is the HBM part)
+    const bool quads = ((p.ld & 3) == 0) && ((h & 3) == 0) && ((((uintptr_t)p.sim) & 15) == 0);
+    for (int i = 4 * tid; i < span; i += 1024) {
         const long t = t0 - h + i;
-        float m = -INFINITY;                         // outside the context: takes no part
-        if (t >= 0 && t < p.N) {
-            m = p.sim[t];
-            for (int q = 1; q < p.nq; ++q) m = fmaxf(m, p.sim[(size_t)q * p.ld + t]);
+        if (quads && t >= 0 && t + 4 <= p.N && i + 4 <= span) {
+            float4 m = *(const float4 *)(p.sim + t);
+#pragma unroll 4
+            for (int q = 1; q < p.nq; ++q) {
+                const float4 v = *(const float4 *)(p.sim + (size_t)q * p.ld + t);
+                m.x = fmaxf(m.x, v.x); m.y = fmaxf(m.y, v.y); m.z = fmaxf(m.z, v.z); m.w = fmaxf(m.w, v.w);
+            }
+            buf[0][i] = m.x; buf[0][i + 1] = m.y; buf[0][i + 2] = m.z; buf[0][i + 3] = m.w;
+        } else {
+            for (int j = 0; j < 4 && i + j < span; ++j) {
+                const long tj = t + j;
+                float m = -INFINITY;                     // outside the context: takes no part
+                if (tj >= 0 && tj < p.N) {
+                    m = p.sim[tj];
+                    for (int q = 1; q < p.nq; ++q) m = fmaxf(m, p.sim[(size_t)q * p.ld + tj]);
+                }
+                buf[0][i + j] = m;
+            }
         }
-        buf[0][i] = m;
     }
     __syncthreads();
     int cur = 0, len = 1;
