@@ -120,6 +120,12 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *desc,
  *     pos      [n_kv_heads][capacity] int32 token ids travelling with the rows, in/out, may be NULL
  *     kept_idx [n_kv_heads][budget] int32 out (first new_len entries per head), may be NULL
  * Supported: head_dim * sizeof(element) must be a multiple of 16; capacity < 2^31.
+ * Device-side status: when rows move in place (row sizes that divide 16 KB), workgroups order
+ * their reads and writes through flags with a bounded wait.  The wait cannot expire unless other
+ * work keeps part of this call's workgroups off the device for seconds; if it does, the call
+ * still ends, the cache content is then undefined, and the first int32 of the workspace, which
+ * such a call clears when it starts, is set to 1.  A caller that wants to know reads that word
+ * once the stream has finished.
  */
 typedef struct {
     uint32_t struct_size;

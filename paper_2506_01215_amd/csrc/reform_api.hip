@@ -245,6 +245,9 @@ static EvictLayout evict_layout(const reform_evict_desc *d)
     // rows whose size divides 16 KB move in place; other sizes go through K/V staging
     L.inplace = row_bytes <= 16384 && (16384 % row_bytes) == 0;
     L.ntile = L.inplace ? (int)(((size_t)d->budget * row_bytes + 16383) / 16384) : 0;
+    // the synchronisation words of the in-place move come first: word 0 of the workspace is its
+    // error word (documented in the header), then the per-stream tickets and the per-tile flags
+    L.sync = off;        off += align_up((size_t)(32 * (1 + 2 * d->n_kv_heads) + 2 * d->n_kv_heads * (L.ntile ? L.ntile : 1)) * sizeof(int));
     L.kept = off;        off += align_up(rows * sizeof(int32_t));
     L.stage_k = off;     off += L.inplace ? 0 : align_up(rows * row_bytes);
     L.stage_v = off;     off += L.inplace ? 0 : align_up(rows * row_bytes);
@@ -254,7 +257,6 @@ static EvictLayout evict_layout(const reform_evict_desc *d)
     L.prefix = off;      off += align_up((size_t)3 * d->n_kv_heads * sizeof(uint32_t));
     L.krem = off;        off += align_up((size_t)3 * d->n_kv_heads * sizeof(int));
     L.blk = off;         off += align_up((size_t)d->n_kv_heads * (L.nblk ? L.nblk : 1) * 2 * sizeof(int));
-    L.sync = off;        off += align_up((size_t)(32 * (1 + 2 * d->n_kv_heads) + 2 * d->n_kv_heads * (L.ntile ? L.ntile : 1)) * sizeof(int));
     L.rank = off;        off += L.inplace ? align_up((size_t)d->n_kv_heads * d->capacity * sizeof(int32_t)) : 0;
     L.total = off;
     return L;

@@ -23,9 +23,16 @@ def run_case(Hkv, d, n, B, cap, dtype, score, n_sink=0, n_recent=0, seed=0, with
     kd, vd, sd = k.to(DEV), v.to(DEV), score.to(DEV)
     pd = pos.to(DEV) if with_pos else None
     kept = torch.full((Hkv, B), -1, dtype=torch.int32, device=DEV) if with_kept else None
-    new_len = binding.reform_evict_topk_compact(kd, vd, sd, n, B, n_sink, n_recent, pos=pd, kept_idx=kept)
+    ws = torch.full((binding.evict_workspace_bytes(binding.evict_desc(kd, n, B, n_sink, n_recent)) + 256,), 0x5a,
+                    dtype=torch.uint8, device=DEV)
+    new_len = binding.reform_evict_topk_compact(kd, vd, sd, n, B, n_sink, n_recent, pos=pd, kept_idx=kept,
+                                                workspace=ws)
     torch.cuda.synchronize()
     assert new_len == min(n, B)
+    if n > B and 16384 % (d * k.element_size()) == 0:
+        # in-place move: the device-side status word (first int32 of the aligned workspace) stays 0
+        off = (-ws.data_ptr()) % 256
+        assert int(ws[off:off + 4].view(torch.int32).item()) == 0
     k2, v2, s2, p2, kept_ref = oracle.evict_compact(to_np(k), to_np(v), to_np(score).astype(np.float64),
                                                     pos.numpy(), n, B, n_sink, n_recent)
     if with_kept:
