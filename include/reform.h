@@ -119,7 +119,7 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *desc,
  *     score    [n_kv_heads][capacity] fp32, in/out; must be finite (no NaN/Inf)
  *     pos      [n_kv_heads][capacity] int32 token ids travelling with the rows, in/out, may be NULL
  *     kept_idx [n_kv_heads][budget] int32 out (first new_len entries per head), may be NULL
- * Supported: head_dim * sizeof(element) must be a multiple of 16; capacity < 2^31.
+ * Supported: head_dim * sizeof(element) must be a multiple of 16; capacity <= 2^31 - 65536.
  * Device-side status: when rows move in place (row sizes that divide 16 KB), workgroups order
  * their reads and writes through flags with a bounded wait.  The wait cannot expire unless other
  * work keeps part of this call's workgroups off the device for seconds; if it does, the call

@@ -71,6 +71,7 @@ reform_status check_evict(const reform_evict_desc *d)
         return REFORM_ERR_INVALID_ARG;
     if ((d->head_dim * elt_size(d->dtype)) % 16) return REFORM_ERR_UNSUPPORTED;
     if (d->n_kv_heads > 65535) return REFORM_ERR_UNSUPPORTED;
+    if ((int64_t)d->capacity > (1ll << 31) - 65536) return REFORM_ERR_UNSUPPORTED;   // room for tile overhang in int32
     return REFORM_OK;
 }
 

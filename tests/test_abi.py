@@ -75,6 +75,7 @@ def test_evict_rejects_bad_arguments():
     assert call(mk(budget=0)) == 1
     assert call(mk(struct_size=8)) == 1
     assert call(mk(head_dim=4)) == 2                      # 8-byte rows
+    assert call(mk(capacity=(1 << 31) - 1000)) == 2       # index arithmetic needs head room below 2^31
     assert call(mk()) == 3                                # eviction needed but no workspace
     need = lib.reform_evict_topk_compact_workspace(ctypes.byref(mk()))
     assert need >= 8 * 100 * 4 + 2 * 8 * 100 * 4                 # kept indices + score/pos staging
@@ -99,6 +100,7 @@ def test_gather_rejects_bad_arguments():
     assert call(mk(radius=-1)) == 1
     assert call(mk(dim=100)) == 2
     assert call(mk(n_ctx=1 << 31, k=16)) == 2
+    assert call(mk(n_ctx=(1 << 31) - 1000, k=16)) == 2     # index arithmetic needs head room below 2^31
     assert call(mk(), fake, None) == 1                    # union_idx without union_count
     assert call(mk()) == 3                                # no workspace
     assert lib.reform_gather_topk_workspace(ctypes.byref(mk())) >= 2 * 4096 * 4
