@@ -95,7 +95,9 @@ reform_status check_gather(const reform_gather_desc *d)
 
 // Row pitch (floats) of the similarity rows inside the workspace: a multiple of 16 bytes for any
 // n_ctx, so that the similarity kernel can store and the selection can load 16-byte quads, and
-// skewed by 4352 bytes so that the query rows a wave writes at once do not sit a power of two apart.
+// skewed by 4352 bytes so that the query rows a wave writes at once do not sit a power of two
+// apart (at 2^20 rows the whole gather call measured 4 % slower without the skew; skews from 256 B
+// to 64 KB measured alike).
 long sim_pitch(int64_t n_ctx) { return (long)((n_ctx + 63) / 64 * 64 + 1088); }
 
 struct GatherLayout {
