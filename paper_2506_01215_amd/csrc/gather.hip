@@ -74,15 +74,16 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
     // by group): measured 1.7 % faster than handing the groups out round-robin over the grid,
     // as long as the similarity rows are not a power of two apart (the workspace pitch is skewed;
     // with a dense 2^20-float pitch the round-robin order was the faster one by 3 %).
-    const long per_wg = ((ngroups_all + gridDim.x - 1) / gridDim.x + 7) / 8 * 8;
+    const long per_wg = ((ngroups_all + gridDim.x - 1) / gridDim.x + 15) / 16 * 16;
     const long ngroups = min(ngroups_all, (long)(blockIdx.x + 1) * per_wg);
-    const long stride = kSimThreads / 64;
+    // a wave takes pairs of adjacent groups (32 rows): g, g+1, then 16 groups further on
+    auto next_grp = [](long g) -> long { return (g & 1) ? g + 2 * (kSimThreads / 64) - 1 : g + 1; };
     const int nks = D / 32;                               // k-steps per row
     const int nchunks = (nks + kChunk - 1) / kChunk;
     const u16 *E = (const u16 *)p.emb;
     const u16 *qsrc = qs + ln * QROW + 8 * lg;
 
-    long grp = (long)blockIdx.x * per_wg + wave;
+    long grp = (long)blockIdx.x * per_wg + 2 * wave;
     if (grp >= ngroups) return;
     auto row_ptr = [&](long g) -> const u16 * {
         long row = g * 16 + ln;
@@ -105,13 +106,14 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
         }
         if (++l_ch == nchunks) {
             l_ch = 0;
-            l_grp += stride;
+            l_grp = next_grp(l_grp);
             if (l_grp < ngroups) l_base = row_ptr(l_grp);
         }
     };
     load_next(cur);
     load_next(nx1);
     f32x4 dot = {0.f, 0.f, 0.f, 0.f}, gram = {0.f, 0.f, 0.f, 0.f};
+    float held[4] = {0.f, 0.f, 0.f, 0.f};
     int ch = 0;                        // compute cursor
     while (grp < ngroups) {
         load_next(nx2);
@@ -140,24 +142,33 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
                 den = den < p.eps ? p.eps : den;
                 out[e] = dot[e] / den;
             }
-            if (ln < p.nq_grp) {
-                float *dst = p.sim + (size_t)(p.q0 + ln) * p.sim_ld + row0 + 4 * lg;
-                if (row0 + 16 <= p.N && ((p.sim_ld & 3) == 0) && ((((uintptr_t)p.sim) & 15) == 0)) {
-                    // one 16-byte store per lane (row0 and 4*lg are multiples of 4); four 4-byte
+            // The results of an even group wait for its odd neighbour, so that the wave writes the
+            // 128 contiguous bytes of each query row back to back (whole cache lines).
+            auto store_group = [&](long r0, const float (&o)[4]) {
+                float *dst = p.sim + (size_t)(p.q0 + ln) * p.sim_ld + r0 + 4 * lg;
+                if (r0 + 16 <= p.N && ((p.sim_ld & 3) == 0) && ((((uintptr_t)p.sim) & 15) == 0)) {
+                    // one 16-byte store per lane (r0 and 4*lg are multiples of 4); four 4-byte
                     // stores cost the kernel 15 % of its time
-                    *(f32x4 *)dst = (f32x4){out[0], out[1], out[2], out[3]};
+                    *(f32x4 *)dst = (f32x4){o[0], o[1], o[2], o[3]};
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (row0 + 4 * lg + e < p.N) dst[e] = out[e];
+                        if (r0 + 4 * lg + e < p.N) dst[e] = o[e];
                 }
+            };
+            if (!(grp & 1) && grp + 1 < ngroups) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) held[e] = out[e];
+            } else if (ln < p.nq_grp) {
+                if (grp & 1) store_group(row0 - 16, held);
+                store_group(row0, out);
             }
             dot = (f32x4){0.f, 0.f, 0.f, 0.f};
             gram = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) { cur[i] = nx1[i]; nx1[i] = nx2[i]; }
-        if (++ch == nchunks) { ch = 0; grp += stride; }
+        if (++ch == nchunks) { ch = 0; grp = next_grp(grp); }
     }
 }
 
