@@ -32,6 +32,10 @@ struct AttnParams {
     int n_row_blocks;
 };
 
+#ifndef RF_MOVE_TILE
+#define RF_MOVE_TILE 16384
+#endif
+constexpr int kMoveTileBytes = RF_MOVE_TILE;   // bytes of destination rows per workgroup of the in-place move
 constexpr int kUnionWordsPerBlock = 256;   // bitmap words per workgroup of the union kernels
 
 // Top-k selection problem: nq rows of N candidates (row stride ld), k winners per row.

@@ -79,7 +79,8 @@ __global__ __launch_bounds__(256) void evict_move(EvictParams p)
 //      an error word.  The stores of step 5 are issued after the poll returned;
 //   5. store the registers to rows [a, b).
 // Traffic: every moved row is read once and written once.
-constexpr int kTileBytes = 16384;
+constexpr int kTileBytes = kMoveTileBytes;
+constexpr int kTilePieces = kTileBytes / 16 / 256;   // 16-byte pieces per thread
 constexpr int kSpinLimit = 1 << 22;
 constexpr int kSyncLine = 32;        // ints per 128-byte line
 
@@ -122,10 +123,10 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
         if (tid == 0) __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
-    v4u data[4];
-    int rows[4];
+    v4u data[kTilePieces];
+    int rows[kTilePieces];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kTilePieces; ++i) {
         const int q = tid + 256 * i;
         const int r = a + q / pieces, c = q % pieces;
         rows[i] = r < b ? r : -1;
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kTilePieces; ++i) {
         if (rows[i] >= 0) {
             const int c = (tid + 256 * i) % pieces;
             *(v4u *)(base + (size_t)rows[i] * p.row_bytes + (size_t)c * 16) = data[i];

@@ -246,8 +246,8 @@ static EvictLayout evict_layout(const reform_evict_desc *d)
     L.nblk = (d->n_valid + 4095) / 4096;
     size_t off = 0;
     // rows whose size divides 16 KB move in place; other sizes go through K/V staging
-    L.inplace = row_bytes <= 16384 && (16384 % row_bytes) == 0;
-    L.ntile = L.inplace ? (int)(((size_t)d->budget * row_bytes + 16383) / 16384) : 0;
+    L.inplace = row_bytes <= (size_t)kMoveTileBytes && ((size_t)kMoveTileBytes % row_bytes) == 0;
+    L.ntile = L.inplace ? (int)(((size_t)d->budget * row_bytes + kMoveTileBytes - 1) / kMoveTileBytes) : 0;
     // the synchronisation words of the in-place move come first: word 0 of the workspace is its
     // error word (documented in the header), then the per-stream tickets and the per-tile flags
     L.sync = off;        off += align_up((size_t)(32 * (1 + 2 * d->n_kv_heads) + 2 * d->n_kv_heads * (L.ntile ? L.ntile : 1)) * sizeof(int));
