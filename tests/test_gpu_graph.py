@@ -1,7 +1,8 @@
-"""The library calls under HIP graph capture: every call only enqueues kernels on the stream it
-is given (no allocation, no synchronisation, no memset nodes), so a layer-step and a gather can
-be captured once and replayed.  Each replay is checked against the eager result on the same
-inputs, with eager work and synchronisations between the replays."""
+"""The library calls under HIP graph capture and on concurrent streams: every call only enqueues
+kernels on the stream it is given (no allocation, no synchronisation, no memset nodes, no state
+kept between calls), so a layer-step and a gather can be captured once and replayed, and two
+streams can run the library at the same time.  Each replay is checked against the eager result
+on the same inputs, with eager work and synchronisations between the replays."""
 import pytest
 import torch
 
@@ -110,3 +111,54 @@ def test_gather_replays_match_eager():
         assert n == int(graphed["uc"].item()) and n > 0
         assert torch.equal(eager["ti"], graphed["ti"]) and torch.equal(eager["ts"], graphed["ts"])
         assert torch.equal(eager["ui"][:n], graphed["ui"][:n])
+
+
+def test_two_streams_with_their_own_workspaces_do_not_interfere():
+    """The library keeps no state between calls: two layer-steps issued on two streams at the
+    same time, each with its own buffers, give what each gives alone."""
+    Hq, Hkv, d, C, B = 8, 2, 128, 2048, 2048
+    M, cap = B, B + C
+    scale = d ** -0.5
+    g = torch.Generator(device=DEV).manual_seed(31)
+    rnd = lambda *s: torch.randn(s, generator=g, device=DEV).bfloat16()
+
+    def make():
+        b = dict(q=rnd(Hq, C, d), K=rnd(Hkv, cap, d), V=rnd(Hkv, cap, d),
+                 pos=torch.arange(cap, dtype=torch.int32, device=DEV).repeat(Hkv, 1).contiguous(),
+                 out=torch.empty((Hq, C, d), dtype=torch.bfloat16, device=DEV),
+                 lse=torch.empty((Hq, C), dtype=torch.float32, device=DEV),
+                 score=torch.empty((Hkv, cap), dtype=torch.float32, device=DEV),
+                 kept=torch.empty((Hkv, B), dtype=torch.int32, device=DEV))
+        b["wsa"] = torch.empty(binding.attend_workspace_bytes(binding.attn_desc(b["q"], b["K"], b["q"], M, scale)) + 512,
+                               dtype=torch.uint8, device=DEV)
+        b["wse"] = torch.empty(binding.evict_workspace_bytes(binding.evict_desc(b["K"], M + C, B)) + 512,
+                               dtype=torch.uint8, device=DEV)
+        return b
+
+    def step(b):
+        binding.reform_chunk_attend_score(b["q"], b["K"], b["V"], M, scale, out=b["out"], lse=b["lse"],
+                                          score=b["score"], workspace=b["wsa"])
+        binding.reform_evict_topk_compact(b["K"], b["V"], b["score"], M + C, B, pos=b["pos"],
+                                          kept_idx=b["kept"], workspace=b["wse"])
+
+    jobs = [make() for _ in range(2)]
+    alone = []
+    for b in jobs:                                        # reference: one after the other
+        ref = {k: v.clone() for k, v in b.items()}
+        step(ref)
+        alone.append(ref)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):                                  # interleaved issue on two streams
+        work = [{k: v.clone() for k, v in b.items()} for b in jobs]
+        torch.cuda.synchronize()
+        for b, st in zip(work, streams):
+            with torch.cuda.stream(st):
+                step(b)
+        torch.cuda.synchronize()
+        for b, ref in zip(work, alone):
+            for name in ("out", "lse", "kept"):
+                assert torch.equal(b[name], ref[name]), (rep, name)
+            for name in ("K", "V"):
+                assert torch.equal(b[name][:, :B], ref[name][:, :B]), (rep, name)
+            assert torch.equal(b["score"][:, :B], ref["score"][:, :B]) and torch.equal(b["pos"][:, :B], ref["pos"][:, :B])
