@@ -57,6 +57,7 @@ struct SelParams {
     int32_t *side_dst;       // ... copied to [nq][out_ld] for the selected ones (same order as out_idx)
     int *zero_extra;         // nullable: zero_extra_n more ints cleared by the histogram-clearing launch
     int zero_extra_n;
+    int pre_zeroed;          // hist and zero_extra were cleared by an earlier kernel of the same call
 };
 
 struct EvictParams {
@@ -170,6 +171,16 @@ __device__ __forceinline__ uint32_t ordered_key(float f)
     uint32_t u = __float_as_uint(f);
     if (u == 0x80000000u) u = 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Clears the selection's histograms and extra ints; thread i0 of `stride` threads.  Called at the
+// start of a kernel that runs before the selection in the same library call, which saves the
+// selection its own clearing launch.
+__device__ __forceinline__ void sel_clear(const SelParams &p, long i0, long stride)
+{
+    const long nh = (long)p.nq * 3 * 2048;
+    for (long i = i0; i < nh; i += stride) p.hist[i] = 0;
+    for (long i = i0; i < p.zero_extra_n; i += stride) p.zero_extra[i] = 0;
 }
 
 // Exclusive scan of one int per thread over a 256-thread workgroup (tmp: 4 ints of LDS);

@@ -42,6 +42,8 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
     const int D = p.D, QROW = sim_qrow(D);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
+    if (p.sel.pre_zeroed && p.q0 == 0)        // the selection that follows finds its histograms cleared
+        sel_clear(p.sel, (long)blockIdx.x * kSimThreads + tid, (long)gridDim.x * kSimThreads);
 
     // stage the (up to 16) queries of this group, zero-padded, and their norms
     const u16 *Q = (const u16 *)p.qry + (size_t)p.q0 * D;
@@ -180,6 +182,8 @@ __global__ __launch_bounds__(256) void sim_generic(GatherParams p)
     __shared__ float qnorm[16];
     const int D = p.D;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (p.sel.pre_zeroed && p.q0 == 0)
+        sel_clear(p.sel, (long)blockIdx.x * 256 + tid, (long)gridDim.x * 256);
     auto ld = [](const T *ptr, size_t i) -> float {
         if constexpr (sizeof(T) == 2) return bf16_bits_to_f32(((const u16 *)ptr)[i]);
         else return ((const float *)ptr)[i];
@@ -351,10 +355,6 @@ hipError_t gather_similarity(GatherParams p, int dtype_is_bf16, hipStream_t st)
 
 hipError_t gather_select_union(GatherParams p, hipStream_t st)
 {
-    if (p.union_idx) {                        // the selection's clearing launch also clears the bitmap
-        p.sel.zero_extra = (int *)p.bitmap;
-        p.sel.zero_extra_n = p.nwords;
-    }
     hipError_t es = select_topk(p.sel, st);
     if (es != hipSuccess) return es;
     if (p.union_idx) {

@@ -376,6 +376,11 @@ reform_status reform_gather_topk(const reform_gather_desc *d, const void *emb, c
     p.sel.blk_cnt = (int *)(ws + L.blk);
     p.sel.nblk = L.nblk;
     p.sel.out_idx = topk_idx; p.sel.out_val = topk_score; p.sel.out_ld = d->k;
+    if (union_idx) {                          // the bitmap is cleared together with the histograms ...
+        p.sel.zero_extra = (int *)p.bitmap;
+        p.sel.zero_extra_n = L.nwords;
+    }
+    p.sel.pre_zeroed = 1;                     // ... by the first similarity launch
     hipStream_t st = (hipStream_t)hip_stream;
     if (gather_similarity(p, d->dtype == REFORM_BF16, st) != hipSuccess) return REFORM_ERR_RUNTIME;
     return gather_select_union(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;

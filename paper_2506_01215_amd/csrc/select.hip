@@ -515,9 +515,11 @@ hipError_t select_topk(const SelParams &p, hipStream_t st)
         RF_CHECK_LAUNCH();
         return hipSuccess;
     }
-    const long nz = max((long)p.nq * 3 * 2048, (long)p.zero_extra_n);
-    hipLaunchKernelGGL(sel_zero, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, p);
-    RF_CHECK_LAUNCH();
+    if (!p.pre_zeroed) {
+        const long nz = max((long)p.nq * 3 * 2048, (long)p.zero_extra_n);
+        hipLaunchKernelGGL(sel_zero, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, p);
+        RF_CHECK_LAUNCH();
+    }
     const dim3 sgrid(p.nblk, p.nq);
     const int hblk = max(1, kHistWorkgroups / p.nq);       // workgroups per row of the histogram passes
     const dim3 hgrid(min(p.nblk, hblk), p.nq);
