@@ -108,3 +108,65 @@ def test_gather_random_shape(seed):
         assert_close(sc.cpu().numpy()[qi], sim_ref[qi][idx_h[qi]], RTOL[dtype], f"scores q={qi}")
     got = uni.cpu().numpy()[:int(cnt.item())]
     np.testing.assert_array_equal(got, numpy_union(idx_h, N, radius, n_head, n_tail))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_selection_random_sizes_across_paths(seed):
+    """Evict (odd seeds) and gather (even seeds) at random sizes from 2 to 200000 candidates per
+    row, so that every variant of the selection is hit (one launch with 4 to 32 keys per lane,
+    several launches), with exact ties, forced slots and unaligned row pitches.  The integer
+    results must match exactly (the gather on the GPU's own similarity values)."""
+    rng = np.random.default_rng(7000 + seed)
+    g = torch.Generator().manual_seed(seed)
+    if seed % 2:
+        Hkv = int(rng.integers(1, 4))
+        n = int([rng.integers(2, 5000), rng.integers(4000, 9000), rng.integers(16000, 17000),
+                 rng.integers(30000, 34000), rng.integers(60000, 70000), rng.integers(100000, 140000)][(seed // 2) % 6])
+        B = int(rng.integers(1, n))
+        d = int(rng.choice([8, 64]))
+        cap = n + int(rng.integers(0, 9))
+        ns = int(rng.integers(0, min(B, 300) + 1)) if rng.random() < 0.4 else 0
+        nr = int(rng.integers(0, min(B - ns, 300) + 1)) if rng.random() < 0.4 else 0
+        k = torch.randn((Hkv, cap, d), generator=g).bfloat16()
+        v = torch.randn((Hkv, cap, d), generator=g).bfloat16()
+        if rng.random() < 0.5:
+            score = torch.randint(0, int(rng.choice([2, 7, 1000])), (Hkv, cap), generator=g).float() * 0.25 - 1.0
+        else:
+            score = torch.randn((Hkv, cap), generator=g)
+        pos = torch.arange(cap, dtype=torch.int32).repeat(Hkv, 1).contiguous()
+        kd, vd, sd, pd = k.to(DEV), v.to(DEV), score.to(DEV), pos.to(DEV)
+        kept = torch.full((Hkv, B), -1, dtype=torch.int32, device=DEV)
+        print(f"[sweep select/evict] seed={seed} Hkv={Hkv} n={n} B={B} d={d} cap={cap} sink={ns} recent={nr}", flush=True)
+        binding.reform_evict_topk_compact(kd, vd, sd, n, B, ns, nr, pos=pd, kept_idx=kept)
+        torch.cuda.synchronize()
+        k2, v2, s2, p2, kept_ref = oracle.evict_compact(to_np(k), to_np(v), to_np(score).astype(np.float64),
+                                                        pos.numpy(), n, B, ns, nr)
+        np.testing.assert_array_equal(kept.cpu().numpy(), kept_ref)
+        np.testing.assert_array_equal(to_np(kd)[:, :B], k2[:, :B])
+        np.testing.assert_array_equal(to_np(vd)[:, :B], v2[:, :B])
+        np.testing.assert_array_equal(sd.cpu().numpy()[:, :B].astype(np.float64), s2[:, :B])
+        np.testing.assert_array_equal(pd.cpu().numpy()[:, :B], p2[:, :B])
+    else:
+        N = int([rng.integers(1, 5000), rng.integers(8000, 9000), rng.integers(30000, 36000),
+                 rng.integers(60000, 200000)][(seed // 2) % 4])
+        D = int(rng.choice([32, 64]))
+        nq = int(rng.integers(1, 20))
+        kk = int(rng.integers(1, N + 1)) if rng.random() < 0.3 else int(rng.integers(1, max(2, N // 10)))
+        r = int(rng.choice([0, 1, 8]))
+        emb = torch.randn((N, D), generator=g).bfloat16()
+        if rng.random() < 0.5:                                    # duplicated rows: exact ties
+            emb[torch.from_numpy(rng.integers(0, N, size=max(1, N // 3)))] = emb[0].clone()
+        qry = torch.randn((nq, D), generator=g).bfloat16()
+        n_tail = 2 if N > 2 else 0
+        print(f"[sweep select/gather] seed={seed} N={N} D={D} nq={nq} k={kk} r={r}", flush=True)
+        ti, ts, ui, uc = binding.reform_gather_topk(emb.to(DEV), qry.to(DEV), kk, r, 1, n_tail)
+        sim = binding.reform_gather_similarity(emb.to(DEV), qry.to(DEV))
+        torch.cuda.synchronize()
+        simn = sim.cpu().numpy()
+        for q in range(nq):
+            ref = np.sort(np.lexsort((np.arange(N), -simn[q].astype(np.float64)))[:kk])
+            np.testing.assert_array_equal(ti[q].cpu().numpy(), ref)
+            np.testing.assert_array_equal(ts[q].cpu().numpy(), simn[q][ref])
+        un = numpy_union(ti.cpu().numpy(), N, r, 1, n_tail)
+        assert int(uc.item()) == len(un)
+        np.testing.assert_array_equal(ui[:len(un)].cpu().numpy(), un)
