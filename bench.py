@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes one attn_fwd_bf16 launch of the default workload moves, from the two rocprofv3 --pmc
 # runs summarised in profiles/attn_fwd_cfg3_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE in KiB per
 # dispatch, each scaled by what the same counter reads for a 1 GiB copy kernel: x2.000 and x1.000).
-FWD_TRAFFIC_BYTES = (1736800 * 2.000 + 266240 * 1.000) * 1024
+FWD_TRAFFIC_BYTES = (1737900 * 2.000 + 266240 * 1.000) * 1024
 
 
 def parse():

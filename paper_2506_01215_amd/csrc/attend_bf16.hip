@@ -13,24 +13,15 @@
 // lane groups once), and the probabilities are already laid out as the B operand of
 // O^T = V^T P^T  once the contraction index is permuted consistently on the V side (the V^T
 // operands are fetched from a row-major V tile with gfx950's transposing LDS load, in that
-// permuted key order).  The forward kernel uses
-// v_mfma_f32_16x16x32_bf16, the score kernel v_mfma_f32_32x32x16_bf16 (it is bound by VALU issue,
-// where the larger tile's fewer MFMA instructions matter more than its higher energy per flop).
-//
-// MFMA 32x32x16 operand layout (wave64): A[m][k]: lane l holds m = l%32, k = 8*(l/32)..+7;
-// B[k][n]: lane l holds n = l%32, k = 8*(l/32)..+7;  C[m][n]: lane l holds n = l%32 and, in
-// accumulator element e, m = 8*(e/4) + 4*(l/32) + e%4.
+// permuted key order).  Both kernels use v_mfma_f32_16x16x32_bf16 (wave64 operand layout:
+// A[m][k]: lane l holds m = l%16, k = 8*(l/16)..+7;  B[k][n]: n = l%16, same k;
+// C[m][n]: lane l holds n = l%16 and, in accumulator element e, m = 4*(l/16) + e).
 #include "common.h"
 
 namespace reform {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ __forceinline__ f32x16 mfma32(v4u a, v4u b, f32x16 c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
-}
 
 // ------------------------------------------------------------------------------------------
 // Global -> register -> LDS staging of one 64-key K/V tile by a workgroup of NT threads: K and V
@@ -471,9 +462,9 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 }
 
 // ------------------------------------------------------------------------------------------
-// Score: a workgroup owns NW*32*KB consecutive keys of one KV head (K^T tile held in registers
+// Score: a workgroup owns NW*16*KB consecutive keys of one KV head (K^T tile held in registers
 // as the A operand) and streams every observing query row of the G heads of the group through
-// LDS.  Per-lane partial column sums are kept for the whole pass and reduced across the 32
+// LDS.  Per-lane partial column sums are kept for the whole pass and reduced across the 16
 // query lanes once at the end, in a fixed order: no atomics, bitwise reproducible, and two cache
 // rows with identical keys get identical scores.
 //
@@ -483,7 +474,7 @@ __global__ __launch_bounds__(kFwdWaves * 64, 2) void attn_fwd_bf16(AttnParams p)
 template <int D, int NT>
 struct QStage {
     static constexpr int QT = 64;
-    static constexpr int QROW = D + 8;
+    static constexpr int QROW = D + 16;
     static constexpr int C8 = D / 8;
     static constexpr int PIECES = QT * C8 / NT;
     static_assert(PIECES >= 1, "tile/threads mismatch");
@@ -534,14 +525,24 @@ struct QStage {
     }
 };
 
+// A wave holds 64 keys (four 16-key blocks) as A operands for the whole pass; query rows stream
+// through LDS as B operands, two 16-row blocks at a time; a lane owns one query column of each
+// block and 4 keys per key block.  The MFMA shape and the operand order were chosen by
+// measurement under the power cap (random bf16 operands): 16x16x32 sustains 2.03 PFLOP/s in a
+// pure MFMA loop against 1.83 for 32x32x16, and an A operand that is held for two MFMAs while B
+// alternates between two registers costs 4 % less than a new A operand on every MFMA.  The
+// 32x32x16 form of this kernel (32 keys x 32 rows per MFMA, new key fragment every MFMA) was
+// 1.2 % slower.
 template <int D, int KB, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
 {
     constexpr int NT = NW * 64;
-    constexpr int KS = D / 16;
+    constexpr int KS = D / 32;                           // MFMA k-steps
     using Stage = QStage<D, NT>;
     constexpr int QT = Stage::QT, QROW = Stage::QROW;
-    constexpr int WKEYS = 32 * KB;
+    constexpr int WKEYS = 16 * KB;
+    constexpr int NQB = QT / 16;                         // 16-row query blocks per tile
+    static_assert(NQB % 4 == 0, "the rotation below alternates two units of two query blocks");
 
     __shared__ __attribute__((aligned(16))) u16 ldsQ[2][QT * QROW];
     __shared__ float ldsL[2][QT];
@@ -549,8 +550,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int ln = lane & 31;
-    const int lg = lane >> 5;
+    const int ln = lane & 15;
+    const int lg = lane >> 4;
 
     const int kvh = blockIdx.x % p.Hkv;
     const int kt = blockIdx.x / p.Hkv;
@@ -561,18 +562,16 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
     v4u kreg[KB][KS];
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
-        int key = jw + kb * 32 + ln;
+        int key = jw + kb * 16 + ln;
         key = key < p.n ? key : p.n - 1;
         const u16 *src = Kg + (size_t)key * D + 8 * lg;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kreg[kb][ks] = *(const v4u *)(src + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) kreg[kb][ks] = *(const v4u *)(src + ks * 32);
     }
 
-    f32x16 col[KB];
+    f32x4 col[KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) col[kb][e] = 0.f;
+    for (int kb = 0; kb < KB; ++kb) col[kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     const int i_lo = p.Ct - p.W;                         // first observing row
     const int i_first = max(i_lo, max(j_wg - p.M, 0));   // first row that both observes and sees j_wg
@@ -595,43 +594,64 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
     if (iters > 1) load_q(1);
     __syncthreads();
 
-    // Rotation inside a wave: the MFMAs of a 32-row block are interleaved, one MFMA to six
-    // VALU instructions, with the v_fma / v_exp / v_add work of the PREVIOUS block, which never
-    // waits for the MFMAs in flight (an MFMA occupies the matrix pipe for about as long as six
-    // such instructions take to issue).  `sB`/`lsB` carry the block whose VALU work is pending;
-    // lsB = +inf makes a block contribute exactly 0 (the empty state).
-    f32x16 sA[KB], sB[KB];                 // sB carries the pending block across iterations
+    // Rotation inside a wave, in units of two adjacent 16-row query blocks: the 32 MFMAs of a unit
+    // are interleaved, one MFMA to three VALU instructions, with the v_fma / v_exp / v_add work of
+    // the PREVIOUS unit, which never waits for the MFMAs in flight.  Every key fragment (A
+    // operand) is used for two MFMAs in a row, the B operand alternating between the unit's two
+    // query blocks.  `sB` / `lsB0`, `lsB1` carry the unit whose VALU work is pending; lse = +inf
+    // makes a block contribute exactly 0 (the empty state).
+    f32x4 sA[2][KB], sB[2][KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sB[kb][e] = 0.f;
-    float lsB = INFINITY;
-    auto issue_mfma = [&](f32x16 (&dst)[KB], const u16 *src) {
-        v4u bq[KS];
+        for (int kb = 0; kb < KB; ++kb) sB[h][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float lsB0 = INFINITY, lsB1 = INFINITY;
+    auto issue_mfma2 = [&](f32x4 (&dst)[2][KB], const u16 *src) {
+        v4u bq0[KS], bq1[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bq[ks] = *(const v4u *)(src + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) {
+            bq0[ks] = *(const v4u *)(src + ks * 32);
+            bq1[ks] = *(const v4u *)(src + 16 * QROW + ks * 32);
+        }
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) dst[kb][e] = 0.f;
+            for (int kb = 0; kb < KB; ++kb) dst[h][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) dst[kb] = mfma32(kreg[kb][ks], bq[ks], dst[kb]);
+            for (int kb = 0; kb < KB; ++kb) {
+                dst[0][kb] = mfma16(kreg[kb][ks], bq0[ks], dst[0][kb]);
+                dst[1][kb] = mfma16(kreg[kb][ks], bq1[ks], dst[1][kb]);
+            }
     };
-    auto accumulate = [&](const f32x16 (&src)[KB], float ls) {
+    auto accumulate2 = [&](const f32x4 (&src)[2][KB], float ls0, float ls1) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) col[kb][e] += __builtin_amdgcn_exp2f(fmaf(src[kb][e], c, -ls));
+            for (int e = 0; e < 4; ++e) {
+                col[kb][e] += __builtin_amdgcn_exp2f(fmaf(src[0][kb][e], c, -ls0));
+                col[kb][e] += __builtin_amdgcn_exp2f(fmaf(src[1][kb][e], c, -ls1));
+            }
     };
-
-    auto interleave_pattern = [&]() {
-        __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
+    f32x4 sD[KB];                          // diagonal path: one 16-row block at a time
+    auto issue_mfma = [&](f32x4 (&dst)[KB], const u16 *src) {
+        v4u bq[KS];
 #pragma unroll
-        for (int u = 0; u < KS * KB; ++u) {
+        for (int ks = 0; ks < KS; ++ks) bq[ks] = *(const v4u *)(src + ks * 32);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) dst[kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) dst[kb] = mfma16(kreg[kb][ks], bq[ks], dst[kb]);
+    };
+    auto interleave_pattern = [&]() {
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * KS, 0);
+#pragma unroll
+        for (int u = 0; u < 2 * KS * KB; ++u) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA ...
-            __builtin_amdgcn_sched_group_barrier(0x402, 6, 0);     // ... then six VALU/transcendental ops
+            __builtin_amdgcn_sched_group_barrier(0x402, 3, 0);     // ... then three VALU/transcendental ops
         }
     };
     for (int it = 0; it < iters; ++it) {
@@ -641,33 +661,39 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
             const u16 *sq = ldsQ[buf] + q_frag0;
             if (jw + WKEYS - 1 <= p.M + i0) {
                 // ---- every row of the tile sees every key of this wave
-                const float ls0 = ldsL[buf][ln], ls1 = ldsL[buf][32 + ln];
-                issue_mfma(sA, sq);
-                accumulate(sB, lsB);
-                interleave_pattern();
-                __builtin_amdgcn_sched_barrier(0);
-                issue_mfma(sB, sq + 32 * QROW);
-                accumulate(sA, ls0);
-                interleave_pattern();
-                __builtin_amdgcn_sched_barrier(0);
-                lsB = ls1;
+#pragma unroll
+                for (int qb = 0; qb < NQB; qb += 4) {
+                    const float l0 = ldsL[buf][16 * qb + ln], l1 = ldsL[buf][16 * qb + 16 + ln];
+                    const float l2 = ldsL[buf][16 * qb + 32 + ln], l3 = ldsL[buf][16 * qb + 48 + ln];
+                    issue_mfma2(sA, sq + 16 * qb * QROW);
+                    accumulate2(sB, lsB0, lsB1);
+                    interleave_pattern();
+                    __builtin_amdgcn_sched_barrier(0);
+                    issue_mfma2(sB, sq + (16 * qb + 32) * QROW);
+                    accumulate2(sA, l0, l1);
+                    interleave_pattern();
+                    __builtin_amdgcn_sched_barrier(0);
+                    lsB0 = l2;
+                    lsB1 = l3;
+                }
             } else {
                 asm volatile("; diagonal path" ::: "memory");
-                accumulate(sB, lsB);                  // flush the pending block first
-                lsB = INFINITY;
+                accumulate2(sB, lsB0, lsB1);          // flush the pending unit first
+                lsB0 = INFINITY;
+                lsB1 = INFINITY;
 #pragma unroll 1
-                for (int qb = 0; qb < 2; ++qb) {
-                    const int r0 = i0 + qb * 32;                 // first row of this 32-row block
-                    if (jw > p.M + r0 + 31) continue;            // no row of the block sees any key
-                    issue_mfma(sA, sq + qb * 32 * QROW);
-                    const float ls = ldsL[buf][qb * 32 + ln];
+                for (int qb = 0; qb < NQB; ++qb) {
+                    const int r0 = i0 + qb * 16;                 // first row of this 16-row block
+                    if (jw > p.M + r0 + 15) continue;            // no row of the block sees any key
+                    issue_mfma(sD, sq + qb * 16 * QROW);
+                    const float ls = ldsL[buf][qb * 16 + ln];
                     const int lim = p.M + r0 + ln - jw;          // key offset <= lim is visible
 #pragma unroll
                     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) {
-                            const int koff = kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
-                            const float pv = __builtin_amdgcn_exp2f(fmaf(sA[kb][e], c, -ls));
+                        for (int e = 0; e < 4; ++e) {
+                            const int koff = kb * 16 + 4 * lg + e;
+                            const float pv = __builtin_amdgcn_exp2f(fmaf(sD[kb][e], c, -ls));
                             col[kb][e] += koff > lim ? 0.f : pv;
                         }
                 }
@@ -679,18 +705,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_score_bf16(AttnParams p)
         }
         __syncthreads();
     }
-    accumulate(sB, lsB);                       // flush the last pending block
+    accumulate2(sB, lsB0, lsB1);               // flush the last pending unit
 
     if (jw >= p.n) return;
     float *dst = p.score + (size_t)kvh * p.cap;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = 0; e < 4; ++e) {
             float x = col[kb][e];
 #pragma unroll
-            for (int off = 16; off >= 1; off >>= 1) x += __shfl_xor(x, off);
-            const int j = jw + kb * 32 + 8 * (e >> 2) + 4 * lg + (e & 3);
+            for (int off = 8; off >= 1; off >>= 1) x += __shfl_xor(x, off);    // over the 16 query lanes
+            const int j = jw + kb * 16 + 4 * lg + e;
             if (ln == 0 && j < p.n) dst[j] = p.accumulate ? dst[j] + x : x;
         }
 }
@@ -719,7 +745,7 @@ static hipError_t launch_fwd(AttnParams p, hipStream_t st)
 template <int D, int KB, int NW>
 static hipError_t launch_score(AttnParams p, hipStream_t st)
 {
-    const int keys_wg = NW * 32 * KB;
+    const int keys_wg = NW * 16 * KB;
     const int grid = p.Hkv * ((p.n + keys_wg - 1) / keys_wg);
     hipLaunchKernelGGL((attn_score_bf16<D, KB, NW>), dim3(grid), dim3(NW * 64), 0, st, p);
     return hipGetLastError();
@@ -733,8 +759,8 @@ hipError_t attend_bf16_forward(const AttnParams &p, hipStream_t st)
 
 hipError_t attend_bf16_score(const AttnParams &p, hipStream_t st)
 {
-    if (p.D == 128) return launch_score<128, 2, 8>(p, st);
-    return launch_score<64, 2, 4>(p, st);
+    if (p.D == 128) return launch_score<128, 4, 8>(p, st);
+    return launch_score<64, 4, 4>(p, st);
 }
 
 }  // namespace reform
