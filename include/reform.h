@@ -143,6 +143,30 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *desc,
                                         void *workspace, size_t workspace_bytes,
                                         void *hip_stream);
 
+/* reform_evict_topk_compact_static -- the same operation for callers that cannot allocate device
+ * memory or carry a workspace: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It takes no workspace: the selection state, the staging rows
+ * and the ordering flags live in a static device array of REFORM_STATIC_SCRATCH_BYTES that each
+ * GPU the library runs on holds until the process ends.  Arguments, layouts, results and status
+ * codes are those of reform_evict_topk_compact; the call allocates and frees nothing.
+ *   - The device the work is meant for must be the current HIP device (the array's address on
+ *     that device is looked up on the first call there).
+ *   - A descriptor whose reform_evict_topk_compact_workspace() exceeds
+ *     REFORM_STATIC_SCRATCH_BYTES is rejected with REFORM_ERR_WORKSPACE before any launch
+ *     (8 KV heads x 65536 candidates -> 32768 of 256-byte rows needs about 5.3 MB).
+ *   - Every call on a GPU shares that GPU's array, which still holds the previous call's
+ *     contents; the call clears what it needs cleared itself.  Two such calls that overlap in
+ *     time on one GPU (different streams or threads) race: serialise them.
+ *   - The device-side status word described above is the first int32 of that array and is not
+ *     reachable by the caller; use the workspace form to observe it.
+ */
+#define REFORM_STATIC_SCRATCH_BYTES (8u << 20)
+
+reform_status reform_evict_topk_compact_static(const reform_evict_desc *desc,
+                                               void *k, void *v, float *score,
+                                               int32_t *pos, int32_t *kept_idx,
+                                               void *hip_stream);
+
 /* ------------------------------------------------------------------------------------------- */
 /* reform_gather_topk
  *

@@ -20,6 +20,7 @@ STATUS = {0: "REFORM_OK", 1: "REFORM_ERR_INVALID_ARG", 2: "REFORM_ERR_UNSUPPORTE
 EXPORTED = [
     "reform_chunk_attend_score_workspace", "reform_chunk_attend_score",
     "reform_evict_topk_compact_workspace", "reform_evict_topk_compact",
+    "reform_evict_topk_compact_static",
     "reform_gather_topk_workspace", "reform_gather_topk", "reform_gather_similarity",
     "reform_gather_pooled_workspace", "reform_gather_pooled", "reform_embed_save_selected",
     "reform_rerotate_keys", "reform_gather_rows",
@@ -111,6 +112,8 @@ def load_library():
     lib.reform_evict_topk_compact_workspace.argtypes = [ctypes.POINTER(EvictDesc)]
     lib.reform_evict_topk_compact.restype = ctypes.c_int
     lib.reform_evict_topk_compact.argtypes = [ctypes.POINTER(EvictDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.reform_evict_topk_compact_static.restype = ctypes.c_int
+    lib.reform_evict_topk_compact_static.argtypes = [ctypes.POINTER(EvictDesc), vp, vp, vp, vp, vp, vp]
     lib.reform_gather_topk_workspace.restype = sz
     lib.reform_gather_topk_workspace.argtypes = [ctypes.POINTER(GatherDesc)]
     lib.reform_gather_topk.restype = ctypes.c_int
@@ -225,6 +228,23 @@ def reform_evict_topk_compact(k, v, score, n_valid, budget, n_sink=0, n_recent=0
                                        _ptr(kept_idx), _ptr(ws), 0 if ws is None else ws.numel(),
                                        _stream(stream))
     _check(rc, "reform_evict_topk_compact")
+    return min(int(n_valid), int(budget))
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def reform_evict_topk_compact_static(k, v, score, n_valid, budget, n_sink=0, n_recent=0, pos=None,
+                                     kept_idx=None, stream=None):
+    """reform_evict_topk_compact without a workspace (the library's static device scratch); the
+    binding allocates nothing either.  k's device must be the current one."""
+    lib = load_library()
+    assert k.is_contiguous() and v.is_contiguous() and score.is_contiguous()
+    assert score.dtype == torch.float32 and score.shape == k.shape[:2]
+    desc = evict_desc(k, n_valid, budget, n_sink, n_recent)
+    rc = lib.reform_evict_topk_compact_static(ctypes.byref(desc), _ptr(k), _ptr(v), _ptr(score),
+                                              _ptr(pos), _ptr(kept_idx), _stream(stream))
+    _check(rc, "reform_evict_topk_compact_static")
     return min(int(n_valid), int(budget))
 
 

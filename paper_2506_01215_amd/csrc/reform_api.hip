@@ -3,6 +3,7 @@
 #include "../../include/reform.h"
 #include "common.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 
@@ -313,6 +314,50 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, voi
     p.sync = L.inplace ? (int *)(ws + L.sync) : nullptr;
     p.ntile = L.ntile;
     return evict_run(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+// The same call for callers that cannot allocate: the workspace is a static device array that
+// every GPU the library runs on holds until the process ends.  `static_scratch` is only a
+// host-side stand-in for the symbol; the device address is looked up once per device with that
+// device current and only that address is ever handed to a kernel.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char static_scratch[REFORM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_static_scratch_ptr[kMaxDevices];
+
+// Device address of static_scratch on the current device (nullptr on failure).  Two threads
+// racing here look up the same address, so the plain atomic store is enough.
+void *static_scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *ptr = g_static_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch)) != hipSuccess || !ptr) return nullptr;
+    g_static_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+}  // namespace
+
+extern "C" {
+
+reform_status reform_evict_topk_compact_static(const reform_evict_desc *d, void *k, void *v,
+                                               float *score, int32_t *pos, int32_t *kept_idx,
+                                               void *hip_stream)
+{
+    const reform_status rc = check_evict(d);
+    if (rc != REFORM_OK) return rc;
+    if (d->n_valid <= d->budget)               // nothing is evicted: no scratch is touched
+        return reform_evict_topk_compact(d, k, v, score, pos, kept_idx, nullptr, 0, hip_stream);
+    if (evict_layout(d).total > (size_t)REFORM_STATIC_SCRATCH_BYTES) return REFORM_ERR_WORKSPACE;
+    void *ws = static_scratch_on_current_device();
+    if (!ws) return REFORM_ERR_RUNTIME;
+    return reform_evict_topk_compact(d, k, v, score, pos, kept_idx, ws,
+                                     (size_t)REFORM_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 // ---------------------------------------------------------------------------------------
