@@ -6,9 +6,9 @@
  *   reform_chunk_attend_score   Alg. 1 `layer.Forward(hs, cache)`, attention part: one chunk of
  *                               queries attends causally over [compressed KV cache || chunk KV]
  *                               (Sec. 3.1, Fig. 1 step 1) and, in the same call, produces the
- *                               attention-based eviction score of every key (Sec. 3.1 "attention-
- *                               based token eviction following H2O"; Sec. 5 names fusing this
- *                               score into the attention kernel as the open efficiency item).
+ *                               eviction score of every key (Sec. 3.1 compresses the cache by
+ *                               evicting on attention weights, as H2O does; Sec. 5 names fusing
+ *                               this score into the attention kernel as the open efficiency item).
  *   reform_evict_topk_compact   Alg. 1 `Compress(cache)`: keep the heavy hitters up to the budget
  *                               and re-pack the cache so retained tokens are consecutive
  *                               (Sec. 3.1, Sec. 1, Sec. 4 common setup).

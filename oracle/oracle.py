@@ -24,6 +24,8 @@ def _lib():
         c_i, c_l, c_d = ctypes.c_int, ctypes.c_int64, ctypes.c_double
         P = ctypes.c_void_p
         lib.oracle_num_threads.restype = c_i
+        lib.oracle_set_num_threads.restype = None
+        lib.oracle_set_num_threads.argtypes = [c_i]
         lib.oracle_attend_score.restype = c_i
         lib.oracle_attend_score.argtypes = [P, P, P, c_i, c_i, c_i, c_i, c_i, c_i, c_d, c_i, c_i,
                                             P, P, P]
@@ -62,6 +64,11 @@ def _ptr(a):
 
 def num_threads():
     return int(_lib().oracle_num_threads())
+
+
+def set_num_threads(n):
+    """OpenMP thread count for later oracle calls made by the calling thread."""
+    _lib().oracle_set_num_threads(int(n))
 
 
 def attend_score(q, k, v, M, scale, W=0, accumulate=False, score_in=None, want_out=True):

@@ -18,7 +18,7 @@
  *     earlier chunks (Fig. 1 step 1, Alg. 1 ForwardChunk), then the cache is
  *     compressed by attention-based token eviction in the manner of H2O,
  *     retained tokens keeping their order (consecutive position ids).
- *   - Sec. 1 ("retaining only the heavy hitters") and Sec. 4 common setup
+ *   - Sec. 1 (only the most influential tokens stay in the cache) and Sec. 4 common setup
  *     (always-kept initial/recent tokens, 128-query observation window of
  *     the H2O implementation).
  *   - Sec. 3.2, the concatenation-of-normalised-heads equation, and Sec. 3.3
@@ -58,6 +58,17 @@ int oracle_num_threads(void)
     return omp_get_max_threads();
 #else
     return 1;
+#endif
+}
+
+/* Thread count of the calling thread's later parallel loops (a test that already
+ * spreads rows over its own threads sets 1).  No arithmetic depends on it.   */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
 #endif
 }
 
@@ -120,7 +131,11 @@ int oracle_attend_score(const float *q, const float *k, const float *v,
     for (int g = 0; g < Hkv; ++g) {
         double *p = (double *)malloc(sizeof(double) * (size_t)n);
         double *o = (double *)malloc(sizeof(double) * (size_t)d);
-        if (!p || !o) { bad = 1; free(p); free(o); continue; }
+        if (!p || !o) {
+#pragma omp atomic write
+            bad = 1;
+            free(p); free(o); continue;
+        }
         const float *kg = k + (size_t)g * cap * d;
         const float *vg = v + (size_t)g * cap * d;
         double *sg = score ? score + (size_t)g * cap : NULL;
@@ -166,7 +181,11 @@ int oracle_attend_rows(const float *q, const float *k, const float *v,
 #pragma omp parallel for schedule(dynamic, 1)
     for (int g = 0; g < Hkv; ++g) {
         double *p = (double *)malloc(sizeof(double) * (size_t)n);
-        if (!p) { bad = 1; continue; }
+        if (!p) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
         double *sg = score ? score + (size_t)g * cap : NULL;
         if (sg)
             for (int j = 0; j < n; ++j) sg[j] = 0.0;

@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import RTOL, assert_close, assert_selection_within_band, to_np
+from helpers import RTOL, BandTally, assert_close, assert_scores_close, assert_selection_within_band, to_np
 from paper_2506_01215_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -30,7 +30,7 @@ def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0, W=0, accumul
     V_all = np.zeros((Hkv, cfg.L, d), np.float32)
     score = torch.zeros((Hkv, cap), dtype=torch.float32, device=DEV)
     acc_ref = np.zeros((Hkv, cfg.L), np.float64)       # accumulate mode: the oracle's own running score per token
-    M, subs_total, stats = 0, 0, []
+    M, subs_total, stats, tally = 0, 0, [], BandTally()
     for t in range(cfg.n_chunks):
         q, k, v = synth.chunk_qkv(cfg, layer, t, plan=plan)
         Ct = q.shape[1]
@@ -90,13 +90,15 @@ def lockstep(cfg, n_sink=0, n_recent=0, check_chunks=None, layer=0, W=0, accumul
                     acc_ref[g, pos_before[g, :n]] = s_ref[g, :n]
             assert_close(to_np(out), o_ref, rtol, f"out chunk {t}")
             assert_close(to_np(lse), l_ref, rtol, f"lse chunk {t}")
-            assert_close(score_gpu[:, :n], s_ref[:, :n], rtol, f"score chunk {t}")
+            assert_scores_close(score_gpu[:, :n], s_ref[:, :n], rtol, f"score chunk {t}")
             for g in range(Hkv):
                 forced = list(range(min(n_sink, n))) + list(range(max(n - n_recent, 0), n)) if n > B else []
                 subs_total += assert_selection_within_band(kept_h[g, :new_len], s_ref[g, :n], new_len,
                                                            rtol, f"kept chunk {t} head {g}", forced)
+                tally.add()
         stats.append(pos_after[:, :new_len].copy())
         M = new_len
+    print(f"[pipeline] {cfg.name}: {tally}", flush=True)
     return stats, subs_total, plan
 
 
