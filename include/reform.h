@@ -143,6 +143,14 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *desc,
                                         void *workspace, size_t workspace_bytes,
                                         void *hip_stream);
 
+/* Testing aid for the device-side status word above.  Sets, for later calls in this process, how
+ * many times a workgroup of the in-place move polls another workgroup's flag before it gives up
+ * (default 2^22; a negative value restores the default).  0 switches publishing off as well, so
+ * every wait on another workgroup expires on its first poll and the status word is set whenever
+ * the kept set makes one tile depend on another: the error path can then be observed while every
+ * kernel still runs to its end.  The cache content after such a call is undefined.            */
+void reform_debug_set_move_spin_limit(int32_t polls);
+
 /* reform_evict_topk_compact_static -- the same operation for callers that cannot allocate device
  * memory or carry a workspace: code running under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  It takes no workspace: the selection state, the staging rows

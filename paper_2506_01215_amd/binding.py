@@ -20,7 +20,7 @@ STATUS = {0: "REFORM_OK", 1: "REFORM_ERR_INVALID_ARG", 2: "REFORM_ERR_UNSUPPORTE
 EXPORTED = [
     "reform_chunk_attend_score_workspace", "reform_chunk_attend_score",
     "reform_evict_topk_compact_workspace", "reform_evict_topk_compact",
-    "reform_evict_topk_compact_static",
+    "reform_evict_topk_compact_static", "reform_debug_set_move_spin_limit",
     "reform_gather_topk_workspace", "reform_gather_topk", "reform_gather_similarity",
     "reform_gather_pooled_workspace", "reform_gather_pooled", "reform_embed_save_selected",
     "reform_rerotate_keys", "reform_gather_rows",
@@ -114,6 +114,8 @@ def load_library():
     lib.reform_evict_topk_compact.argtypes = [ctypes.POINTER(EvictDesc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.reform_evict_topk_compact_static.restype = ctypes.c_int
     lib.reform_evict_topk_compact_static.argtypes = [ctypes.POINTER(EvictDesc), vp, vp, vp, vp, vp, vp]
+    lib.reform_debug_set_move_spin_limit.restype = None
+    lib.reform_debug_set_move_spin_limit.argtypes = [ctypes.c_int32]
     lib.reform_gather_topk_workspace.restype = sz
     lib.reform_gather_topk_workspace.argtypes = [ctypes.POINTER(GatherDesc)]
     lib.reform_gather_topk.restype = ctypes.c_int
@@ -155,14 +157,32 @@ def _stream(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def _workspace(nbytes, device, workspace):
+def _workspace(nbytes, device, workspace, stream=None):
     if nbytes == 0:
         return None
     if workspace is None:
         workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        if stream is not None:
+            # a temporary that is dropped on return while the kernels are only enqueued: tell the
+            # caching allocator which stream still uses the block
+            workspace.record_stream(stream)
     off = (-workspace.data_ptr()) % 256
     ws = workspace[off:]
     return ws
+
+
+def debug_set_move_spin_limit(polls):
+    """Testing aid, see include/reform.h: polls of the in-place move's bounded wait (0 forces the
+    give-up branch, a negative value restores the default)."""
+    load_library().reform_debug_set_move_spin_limit(int(polls))
+
+
+def evict_status_word(workspace):
+    """The device-side status word of reform_evict_topk_compact (first int32 of the 256-byte
+    aligned workspace the caller passed): 0 unless the in-place move's bounded wait expired.
+    Reads it back, so it synchronises with the device."""
+    off = (-workspace.data_ptr()) % 256
+    return int(workspace[off:off + 4].view(torch.int32).item())
 
 
 def _check(rc, where):
@@ -196,7 +216,7 @@ def reform_chunk_attend_score(q, k, v, cache_len, scale, obs_window=0, accumulat
         score = torch.zeros(k.shape[:2], dtype=torch.float32, device=q.device)
     desc = attn_desc(q, k, out, cache_len, scale, obs_window, accumulate, phases)
     need = lib.reform_chunk_attend_score_workspace(ctypes.byref(desc))
-    ws = _workspace(need, q.device, workspace)
+    ws = _workspace(need, q.device, workspace, stream)
     rc = lib.reform_chunk_attend_score(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
                                        _ptr(lse), _ptr(score), _ptr(ws),
                                        0 if ws is None else ws.numel(), _stream(stream))
@@ -223,7 +243,7 @@ def reform_evict_topk_compact(k, v, score, n_valid, budget, n_sink=0, n_recent=0
         assert kept_idx.shape == (k.shape[0], budget)
     desc = evict_desc(k, n_valid, budget, n_sink, n_recent)
     need = lib.reform_evict_topk_compact_workspace(ctypes.byref(desc))
-    ws = _workspace(need, k.device, workspace)
+    ws = _workspace(need, k.device, workspace, stream)
     rc = lib.reform_evict_topk_compact(ctypes.byref(desc), _ptr(k), _ptr(v), _ptr(score), _ptr(pos),
                                        _ptr(kept_idx), _ptr(ws), 0 if ws is None else ws.numel(),
                                        _stream(stream))
@@ -275,7 +295,7 @@ def reform_gather_topk(emb, qry, k, radius=0, n_head_keep=0, n_tail_keep=0, eps=
             union_count = torch.zeros((1,), dtype=torch.int32, device=dev)
     desc = gather_desc(emb, qry, k, radius, n_head_keep, n_tail_keep, eps)
     need = lib.reform_gather_topk_workspace(ctypes.byref(desc))
-    ws = _workspace(need, dev, workspace)
+    ws = _workspace(need, dev, workspace, stream)
     rc = lib.reform_gather_topk(ctypes.byref(desc), _ptr(emb), _ptr(qry), _ptr(topk_idx),
                                 _ptr(topk_score), _ptr(union_idx), _ptr(union_count), _ptr(ws),
                                 0 if ws is None else ws.numel(), _stream(stream))
@@ -360,7 +380,7 @@ def reform_gather_pooled(emb, qry, budget, pool_window=129, n_head_keep=0, n_tai
         pooled = torch.empty((emb.shape[0],), dtype=torch.float32, device=dev)
     desc = pooled_desc(emb, qry, budget, pool_window, n_head_keep, n_tail_keep, eps)
     need = lib.reform_gather_pooled_workspace(ctypes.byref(desc))
-    ws = _workspace(need, dev, workspace)
+    ws = _workspace(need, dev, workspace, stream)
     rc = lib.reform_gather_pooled(ctypes.byref(desc), _ptr(emb), _ptr(qry), _ptr(sel_idx), _ptr(pooled),
                                   _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
     _check(rc, "reform_gather_pooled")

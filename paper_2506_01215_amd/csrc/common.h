@@ -71,6 +71,7 @@ struct EvictParams {
     SelParams sel;             // top-B over score
     int *sync;                 // in-place move: error word, per-stream tickets, per-tile flags; null = staged move
     int ntile;                 // tiles per stream of the in-place move
+    int spin_limit;            // polls a tile spends on another tile's flag before giving up (0: see the kernel)
     int Hkv, n, B, cap, n_sink, n_recent;
     int row_bytes;      // head_dim * sizeof(element), multiple of 16
 };

@@ -81,7 +81,6 @@ __global__ __launch_bounds__(256) void evict_move(EvictParams p)
 // Traffic: every moved row is read once and written once.
 constexpr int kTileBytes = kMoveTileBytes;
 constexpr int kTilePieces = kTileBytes / 16 / 256;   // 16-byte pieces per thread
-constexpr int kSpinLimit = 1 << 22;
 constexpr int kSyncLine = 32;        // ints per 128-byte line
 
 __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
@@ -119,8 +118,11 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
     int *flag = flags + (size_t)stream * p.ntile;
     char *base = (char *)((stream & 1) ? p.v : p.k) + (size_t)g * p.cap * p.row_bytes;
 
+    // spin_limit 0 is the host's way to exercise the give-up branch: no tile publishes and every
+    // wait on another tile expires on its first poll, so the kernel still runs to its end
+    const bool publish = p.spin_limit > 0;
     if (kept[b - 1] == b - 1) {                           // kept[r] == r for every r < b: nothing moves
-        if (tid == 0) __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0 && publish) __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     v4u data[kTilePieces];
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
     asm volatile("" ::: "memory");
     __syncthreads();                                      // ... and of every wave of the tile
     if (tid == 0) {
-        __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (publish) __hip_atomic_store(&flag[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // readers of rows [a, b): dest rows lo .. hi-1 with lo = rank(a), hi = rank(b)
         const int32_t *rank = p.sel.out_rank + (size_t)g * p.cap;
         const int lo = rank[a], hi = rank[b];             // b <= B < n: inside the candidate range
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(256) void evict_move_inplace(EvictParams p)
                 if (t2 == tile) continue;
                 int spins = 0;
                 while (__hip_atomic_load(&flag[t2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-                    if (++spins > kSpinLimit) { atomicExch(p.sync, 1); break; }
+                    if (++spins > p.spin_limit) { atomicExch(p.sync, 1); break; }
                     __builtin_amdgcn_s_sleep(4);
                 }
             }

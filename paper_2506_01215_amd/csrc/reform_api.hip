@@ -233,6 +233,14 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *d, const void *q
 }
 
 // ---------------------------------------------------------------------------------------
+// Polls of the in-place move's bounded wait (see reform_debug_set_move_spin_limit).
+static std::atomic<int> g_move_spin_limit{1 << 22};
+
+void reform_debug_set_move_spin_limit(int32_t polls)
+{
+    g_move_spin_limit.store(polls < 0 ? (1 << 22) : polls, std::memory_order_relaxed);
+}
+
 struct EvictLayout {
     size_t kept, stage_k, stage_v, stage_score, stage_pos, hist, prefix, krem, blk, sync, rank, total;
     int nblk, ntile;
@@ -313,6 +321,7 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, voi
     p.sel.out_rank = L.inplace ? (int32_t *)(ws + L.rank) : nullptr;
     p.sync = L.inplace ? (int *)(ws + L.sync) : nullptr;
     p.ntile = L.ntile;
+    p.spin_limit = g_move_spin_limit.load(std::memory_order_relaxed);
     return evict_run(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 

@@ -101,3 +101,20 @@ def test_band_accepts_only_exact_ties_when_threshold_is_zero():
     assert assert_selection_within_band(np.array([0, 3, 4]), s, 3, 2e-2) == 1    # another zero: in band
     with pytest.raises(AssertionError):
         assert_selection_within_band(np.array([0, 3, 5]), s, 3, 2e-2)
+
+
+def test_threaded_oracle_front_end_equals_the_plain_call():
+    """oracle_kv_heads_dense only spreads rows over threads: same numbers as oracle.attend_score."""
+    from helpers import oracle_kv_heads_dense
+    rng = np.random.default_rng(3)
+    Hq, Hkv, d, M, Ct = 8, 4, 32, 37, 53
+    q = rng.standard_normal((Hq, Ct, d)).astype(np.float32)
+    K = rng.standard_normal((Hkv, M + Ct + 3, d)).astype(np.float32)
+    V = rng.standard_normal((Hkv, M + Ct + 3, d)).astype(np.float32)
+    o_ref, l_ref, s_ref = oracle.attend_score(q, K, V, M, 0.2)
+    for heads in ([2], [0, 3]):
+        o, l, s = oracle_kv_heads_dense(q, K, V, M, 0.2, heads, threads=3)
+        qh = np.concatenate([np.arange(g * 2, g * 2 + 2) for g in heads])
+        np.testing.assert_array_equal(o, o_ref[qh])
+        np.testing.assert_array_equal(l, l_ref[qh])
+        np.testing.assert_allclose(s, s_ref[heads][:, :M + Ct], rtol=1e-13, atol=0)

@@ -31,8 +31,7 @@ def run_case(Hkv, d, n, B, cap, dtype, score, n_sink=0, n_recent=0, seed=0, with
     assert new_len == min(n, B)
     if n > B and 16384 % (d * k.element_size()) == 0:
         # in-place move: the device-side status word (first int32 of the aligned workspace) stays 0
-        off = (-ws.data_ptr()) % 256
-        assert int(ws[off:off + 4].view(torch.int32).item()) == 0
+        assert binding.evict_status_word(ws) == 0
     k2, v2, s2, p2, kept_ref = oracle.evict_compact(to_np(k), to_np(v), to_np(score).astype(np.float64),
                                                     pos.numpy(), n, B, n_sink, n_recent)
     if with_kept:
@@ -165,3 +164,25 @@ def test_row_size_that_needs_the_staged_path():
 def test_full_size_layer_step():
     """Workload 3's shape: 8 KV heads, 65536 candidates -> 32768, head_dim 128 bf16."""
     run_case(8, 128, 65536, 32768, 65536, torch.bfloat16, rand_scores(8, 65536, 77, ties=False), seed=3)
+
+
+def test_bounded_wait_gives_up_and_reports():
+    """The in-place move's give-up branch, forced from the host: with a poll limit of 0 no tile
+    publishes and every wait on another tile expires at once, so the call still ends (every kernel
+    runs to completion) and the status word says that the cache is not to be trusted.  With the
+    default limit restored the same problem is exact again and the word stays 0."""
+    Hkv, n, B, d = 2, 8192, 4096, 128
+    s = (torch.arange(n) % 2).float().repeat(Hkv, 1).contiguous()     # keeps every other row: tiles depend on earlier tiles
+    g = torch.Generator().manual_seed(11)
+    k = torch.randn((Hkv, n, d), generator=g).bfloat16().to(DEV)
+    v = torch.randn((Hkv, n, d), generator=g).bfloat16().to(DEV)
+    ws = torch.zeros((binding.evict_workspace_bytes(binding.evict_desc(k, n, B)) + 256,), dtype=torch.uint8, device=DEV)
+    print("[evict] forced give-up of the bounded wait", flush=True)
+    binding.debug_set_move_spin_limit(0)
+    try:
+        binding.reform_evict_topk_compact(k, v, s.to(DEV), n, B, workspace=ws)
+        torch.cuda.synchronize()
+        assert binding.evict_status_word(ws) == 1
+    finally:
+        binding.debug_set_move_spin_limit(-1)
+    run_case(Hkv, d, n, B, n, torch.bfloat16, s)                        # asserts exact results and a clear status word
