@@ -342,6 +342,25 @@ reform_status reform_gather_rows(const reform_rows_desc *desc, const void *table
                                  const int32_t *idx, const int32_t *count, void *out,
                                  int32_t *err, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------- */
+/* Measurement aids (no step of the method): what this machine sustains on the resources the
+ * kernels above are bound by, so a benchmark can quote a kernel against the measured ceiling as
+ * well as against the data-sheet one.
+ *
+ * reform_probe_mfma_bf16: `workgroups` workgroups of 8 waves each run `iters` trips of 16
+ *   v_mfma_f32_16x16x32_bf16 (4 x 4 operand registers, all combinations) and nothing else;
+ *   executed flop = workgroups * 8 * iters * 16 * 16384.  `operands`: 64 KiB of device memory
+ *   holding the bf16 values to multiply (random data heats the chip like real inputs, zeros do
+ *   not); `sink`: 16 bytes of device memory that is practically never written.
+ * reform_probe_stream: reads `bytes` (a multiple of 16) from src with 16-byte loads and, if dst is
+ *   not NULL, stores them to dst (a plain copy: bytes read + bytes written); with dst == NULL it
+ *   is a read-only stream.  `sink` as above.
+ * Both only enqueue one kernel on hip_stream.                                                   */
+reform_status reform_probe_mfma_bf16(const void *operands, float *sink, int32_t iters,
+                                     int32_t workgroups, void *hip_stream);
+reform_status reform_probe_stream(const void *src, void *dst, size_t bytes, void *sink,
+                                  void *hip_stream);
+
 const char *reform_status_string(reform_status status);
 
 /* Library version, major*10000 + minor*100 + patch.                                            */

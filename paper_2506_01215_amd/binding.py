@@ -23,7 +23,7 @@ EXPORTED = [
     "reform_evict_topk_compact_static", "reform_debug_set_move_spin_limit",
     "reform_gather_topk_workspace", "reform_gather_topk", "reform_gather_similarity",
     "reform_gather_pooled_workspace", "reform_gather_pooled", "reform_embed_save_selected",
-    "reform_rerotate_keys", "reform_gather_rows",
+    "reform_rerotate_keys", "reform_gather_rows", "reform_probe_mfma_bf16", "reform_probe_stream",
     "reform_status_string", "reform_version",
 ]
 
@@ -132,6 +132,10 @@ def load_library():
     lib.reform_rerotate_keys.argtypes = [ctypes.POINTER(RopeDesc), vp, vp, vp]
     lib.reform_gather_rows.restype = ctypes.c_int
     lib.reform_gather_rows.argtypes = [ctypes.POINTER(RowsDesc), vp, vp, vp, vp, vp, vp]
+    lib.reform_probe_mfma_bf16.restype = ctypes.c_int
+    lib.reform_probe_mfma_bf16.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp]
+    lib.reform_probe_stream.restype = ctypes.c_int
+    lib.reform_probe_stream.argtypes = [vp, vp, sz, vp, vp]
     lib.reform_status_string.restype = ctypes.c_char_p
     lib.reform_status_string.argtypes = [ctypes.c_int]
     lib.reform_version.restype = ctypes.c_int32
@@ -401,3 +405,21 @@ def evict_workspace_bytes(desc):
 
 def gather_workspace_bytes(desc):
     return load_library().reform_gather_topk_workspace(ctypes.byref(desc))
+
+
+def probe_mfma_bf16(operands, sink, iters, workgroups, stream=None):
+    """Measurement aid: a pure bf16 MFMA loop; returns the flop it executes."""
+    assert operands.numel() * operands.element_size() >= 65536 and sink.numel() * sink.element_size() >= 16
+    rc = load_library().reform_probe_mfma_bf16(_ptr(operands), _ptr(sink), int(iters), int(workgroups),
+                                               _stream(stream))
+    _check(rc, "reform_probe_mfma_bf16")
+    return float(workgroups) * 8 * iters * 16 * 16384
+
+
+def probe_stream(src, dst, sink, stream=None):
+    """Measurement aid: read src (and copy it to dst unless dst is None); returns the bytes moved."""
+    nbytes = src.numel() * src.element_size()
+    assert src.is_contiguous() and (dst is None or (dst.is_contiguous() and dst.numel() * dst.element_size() >= nbytes))
+    rc = load_library().reform_probe_stream(_ptr(src), _ptr(dst), nbytes, _ptr(sink), _stream(stream))
+    _check(rc, "reform_probe_stream")
+    return float(nbytes) * (1 if dst is None else 2)

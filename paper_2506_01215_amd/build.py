@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libreform_hip.so")
-SOURCES = ["reform_api.hip", "attend_bf16.hip", "attend_f32.hip", "evict.hip", "gather.hip", "select.hip", "pool.hip", "embed.hip", "rope.hip", "rows.hip"]
+SOURCES = ["reform_api.hip", "attend_bf16.hip", "attend_f32.hip", "evict.hip", "gather.hip", "select.hip", "pool.hip", "embed.hip", "rope.hip", "rows.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -23,6 +23,8 @@ int gather_pool_max_window();
 hipError_t embed_save(const EmbedParams &p, bool bf16, hipStream_t st);
 hipError_t rope_rerotate_launch(const RopeParams &p, bool bf16, hipStream_t st);
 hipError_t gather_rows_launch(const RowsParams &p, hipStream_t st);
+hipError_t probe_mfma_launch(const void *operands, float *sink, int iters, int workgroups, hipStream_t st);
+hipError_t probe_stream_launch(const void *src, void *dst, size_t bytes, void *sink, hipStream_t st);
 }  // namespace reform
 
 using namespace reform;
@@ -561,6 +563,22 @@ reform_status reform_gather_rows(const reform_rows_desc *d, const void *table, c
     p.table = table; p.out = out; p.idx = idx; p.count = count; p.err = err;
     p.n_table = d->n_table; p.n_idx = d->n_idx; p.row_bytes = d->row_bytes; p.pieces = d->row_bytes / 16;
     return gather_rows_launch(p, (hipStream_t)hip_stream) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+// ---------------------------------------------------------------------------------------
+reform_status reform_probe_mfma_bf16(const void *operands, float *sink, int32_t iters,
+                                     int32_t workgroups, void *hip_stream)
+{
+    if (!operands || !sink || iters <= 0 || workgroups <= 0 || !aligned16(operands)) return REFORM_ERR_INVALID_ARG;
+    return probe_mfma_launch(operands, sink, iters, workgroups, (hipStream_t)hip_stream) == hipSuccess
+               ? REFORM_OK : REFORM_ERR_RUNTIME;
+}
+
+reform_status reform_probe_stream(const void *src, void *dst, size_t bytes, void *sink, void *hip_stream)
+{
+    if (!src || !sink || (bytes % 16) || !aligned16(src) || !aligned16(dst)) return REFORM_ERR_INVALID_ARG;
+    return probe_stream_launch(src, dst, bytes, sink, (hipStream_t)hip_stream) == hipSuccess
+               ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 
 }  // extern "C"
