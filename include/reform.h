@@ -125,7 +125,10 @@ reform_status reform_chunk_attend_score(const reform_attn_desc *desc,
  * work keeps part of this call's workgroups off the device for seconds; if it does, the call
  * still ends, the cache content is then undefined, and the first int32 of the workspace, which
  * such a call clears when it starts, is set to 1.  A caller that wants to know reads that word
- * once the stream has finished.
+ * once the stream has finished.  Rows of more than 32768 candidates are selected by several
+ * workgroups per row that wait for each other inside one launch (at most 128 workgroups, half of
+ * what the chip holds at once); the same bounded wait and status word cover it, and more than two
+ * such calls overlapping on one GPU from different streams are the one way to make it expire.
  */
 typedef struct {
     uint32_t struct_size;

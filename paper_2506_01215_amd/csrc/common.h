@@ -58,6 +58,11 @@ struct SelParams {
     int *zero_extra;         // nullable: zero_extra_n more ints cleared by the histogram-clearing launch
     int zero_extra_n;
     int pre_zeroed;          // hist and zero_extra were cleared by an earlier kernel of the same call
+    int multi_ok;            // rows too long for one workgroup may be selected in one launch by several
+                             // workgroups that wait for each other (needs hist, blk_cnt and err to be usable
+                             // for that: the eviction sets it)
+    int *err;                // nullable: set to 1 if a bounded wait between workgroups expired
+    int spin_limit;          // polls of such a wait
 };
 
 struct EvictParams {

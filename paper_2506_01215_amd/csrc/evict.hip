@@ -181,6 +181,7 @@ hipError_t evict_run(const EvictParams &p, hipStream_t st)
         sel.side_dst = p.pos ? p.stage_pos : nullptr;
         sel.zero_extra = p.sync;
         sel.zero_extra_n = kSyncLine * (1 + p.Hkv * 2) + p.Hkv * 2 * p.ntile;
+        sel.err = p.sync;                       // the call's status word
         hipError_t e = select_topk(sel, st);
         if (e != hipSuccess) return e;
         const int side_blocks = p.Hkv * ((p.B + 255) / 256);

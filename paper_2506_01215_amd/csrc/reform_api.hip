@@ -321,6 +321,8 @@ reform_status reform_evict_topk_compact(const reform_evict_desc *d, void *k, voi
     p.sel.nblk = L.nblk;
     p.sel.out_idx = p.kept; p.sel.out_val = nullptr; p.sel.out_ld = d->budget;
     p.sel.out_rank = L.inplace ? (int32_t *)(ws + L.rank) : nullptr;
+    p.sel.multi_ok = 1;
+    p.sel.spin_limit = g_move_spin_limit.load(std::memory_order_relaxed);
     p.sync = L.inplace ? (int *)(ws + L.sync) : nullptr;
     p.ntile = L.ntile;
     p.spin_limit = g_move_spin_limit.load(std::memory_order_relaxed);

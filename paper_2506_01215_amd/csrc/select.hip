@@ -12,6 +12,8 @@
 //   select_write  ordered emission: everything above the threshold, then the lowest-index ties
 //   select_fused  rows of at most 32768 candidates: all of the above in one launch, one workgroup
 //                 per row, keys held in registers
+//   select_multi  longer rows, when every workgroup of the launch fits on the chip at once: one
+//                 launch, several workgroups per row that meet at four counted barriers
 // Candidates in the first n_sink or last n_recent slots get the maximal key (always selected).
 #include "common.h"
 
@@ -43,6 +45,7 @@ __global__ void sel_zero(SelParams p)
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < (long)p.nq * 3 * 2048) p.hist[i] = 0;
     if (i < p.zero_extra_n) p.zero_extra[i] = 0;
+    if (p.multi_ok && i < (long)p.nq * p.nblk * 2) p.blk_cnt[i] = 0;
 }
 
 __device__ __forceinline__ int digit_of(uint32_t u, int pass)
@@ -333,7 +336,7 @@ __device__ __forceinline__ void range_emit(const SelParams &p, int q, const uint
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (keep[j] && dest < p.k) {
+            if (keep[j] && (unsigned)dest < (unsigned)p.k) {
                 oi[dest] = (int32_t)(t + j);
                 if (os) os[dest] = val[j];
                 if (ss) sd[dest] = side[j];
@@ -499,6 +502,172 @@ __global__ __launch_bounds__(1024) void select_fused(SelParams p)
     else range_emit<NIT, false>(p, q, u, N, w_lo, T, need_eq, dest_run, base_eq);
 }
 
+// ------------------------------------------------------------------------------------------
+// Rows longer than that, in ONE launch when the whole grid can be resident at once: `parts`
+// workgroups of 1024 threads share a row, each holding NIT * 4096 of its candidates in registers
+// for the whole selection.  Per radix pass a workgroup merges its LDS histogram into the row's
+// global histogram (cleared by the launch before) with integer atomics and then polls that
+// histogram until its total equals the number of candidates the pass must see -- all N in the
+// first pass, afterwards the count of the bin picked by the pass before -- so the merged histogram
+// is its own completion signal and no separate barrier is paid.  Every workgroup of a row takes
+// the same pick from the same numbers.  The per-workgroup counts of candidates above / equal to
+// the threshold are published as count + 1 into cleared words, which the later workgroups of the
+// row poll for; from them each workgroup derives where its share of the ascending output starts.
+// Results are identical to the other two paths.
+//
+// Everything that crosses workgroups inside the launch goes through agent-scope atomics (adds,
+// loads, stores), which are performed beyond the per-XCD L2s.  The waits are bounded: the host
+// launches this kernel only with at most kMultiMaxGroups workgroups, half of what the chip's 256
+// compute units hold at once even at one such workgroup each, so every workgroup that is waited
+// for is running or will be dispatched as soon as unrelated work drains; if a limit is reached
+// all the same (more than two such launches overlapping on different streams could do that), the
+// kernel still ends, sets *err and leaves undefined output.
+constexpr int kMultiMaxGroups = 128;
+
+// All 1024 threads: poll the row's histogram of a pass (thread t owns digits 2t, 2t+1) until it
+// holds `expected` candidates, then leave that snapshot in h.
+__device__ __forceinline__ void multi_wait_hist(const int *gh, int ndigits, int expected, int *h, int *wtot,
+                                                int spin_limit, int *err)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int v0 = 0, v1 = 0;
+    for (int spins = 0;; ++spins) {
+        if (2 * tid < ndigits) {
+            v0 = __hip_atomic_load(&gh[2 * tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v1 = __hip_atomic_load(&gh[2 * tid + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        int sum = v0 + v1;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+        if (lane == 0) wtot[wave] = sum;
+        __syncthreads();
+        int total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) total += wtot[w];
+        __syncthreads();                                  // wtot is rewritten by the next poll
+        if (total == expected) break;
+        if (spins >= spin_limit) {                        // uniform: every thread saw the same total
+            if (tid == 0 && err) atomicExch(err, 1);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    h[2 * tid] = v0;
+    h[2 * tid + 1] = v1;
+    __syncthreads();
+}
+
+// fused_pick that also reports how many candidates the picked digit holds (sel[2]).
+template <int PASS>
+__device__ __forceinline__ void multi_pick(uint32_t &prefix, int &krem, int &in_bin, const int *h, int *wtot, int *sel)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l0 = h[2 * tid], l1 = h[2 * tid + 1], sum = l0 + l1;
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(incl, o);
+        if (lane >= o) incl += y;
+    }
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    int below = incl - sum, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const int x = wtot[w];
+        if (w < wave) below += x;
+        total += x;
+    }
+    const int above = total - below - sum;                    // candidates with a digit above 2t+1
+    if (above < krem && krem <= above + l1) { sel[0] = 2 * tid + 1; sel[1] = krem - above; sel[2] = l1; }
+    else if (above + l1 < krem && krem <= above + sum) { sel[0] = 2 * tid; sel[1] = krem - above - l1; sel[2] = l0; }
+    __syncthreads();
+    prefix = (prefix << (PASS == 2 ? 10 : 11)) | (uint32_t)sel[0];
+    krem = sel[1];
+    in_bin = sel[2];
+    __syncthreads();
+}
+
+template <int NIT>
+__global__ __launch_bounds__(1024) void select_multi(SelParams p, int parts)
+{
+    __shared__ int h[2048];
+    __shared__ int wtot[2][16];
+    __shared__ int sel[3];
+    __shared__ int before[2];
+    const int q = blockIdx.x / parts, part = blockIdx.x % parts;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 3) sel[tid] = 0;
+    if (tid < 2) before[tid] = 0;
+
+    const float *s = p.vals + (size_t)q * p.ld;
+    const int N = (int)p.N;
+    const int w_lo = part * (NIT * 4096) + wave * (NIT * 256);
+    const bool full = w_lo + NIT * 256 <= N;
+    uint32_t u[NIT][4];
+    range_keys<NIT>(p, s, N, w_lo, u);
+
+    uint32_t prefix = 0u;
+    int krem = p.k;
+    int expected = N;                                             // candidates the coming pass counts
+#define RF_MULTI_PASS(PASS)                                                                  \
+    {                                                                                        \
+        for (int i = tid; i < 2048; i += 1024) h[i] = 0;                                     \
+        __syncthreads();                                                                     \
+        if (full) fused_hist<NIT, PASS, true>(u, N, w_lo, prefix, h);                        \
+        else fused_hist<NIT, PASS, false>(u, N, w_lo, prefix, h);                            \
+        __syncthreads();                                                                     \
+        int *gh = p.hist + ((size_t)q * 3 + PASS) * 2048;                                    \
+        for (int i = tid; i < 2048; i += 1024)                                               \
+            if (h[i]) atomicAdd(&gh[i], h[i]);                                               \
+        __syncthreads();                                                                     \
+        multi_wait_hist(gh, PASS == 2 ? 1024 : 2048, expected, h, wtot[0], p.spin_limit, p.err); \
+        multi_pick<PASS>(prefix, krem, expected, h, wtot[0], sel);                           \
+    }
+    RF_MULTI_PASS(0)
+    RF_MULTI_PASS(1)
+    RF_MULTI_PASS(2)
+#undef RF_MULTI_PASS
+    const uint32_t T = prefix;
+    const int need_eq = max(krem, 0);
+
+    int gt_w, eq_w;
+    if (full) range_count<NIT, true>(u, N, w_lo, T, gt_w, eq_w);
+    else range_count<NIT, false>(u, N, w_lo, T, gt_w, eq_w);
+    if (lane == 0) { wtot[0][wave] = gt_w; wtot[1][wave] = eq_w; }
+    __syncthreads();
+    int *c = p.blk_cnt + (size_t)q * parts * 2;                   // cleared words: 0 = not published yet
+    if (tid < 2) {
+        int tot = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) tot += wtot[tid][w];
+        __hip_atomic_store(&c[2 * part + tid], tot + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // candidates above / equal to T in the workgroups before this one (2 * parts <= 256 < 1024 threads)
+    if (tid < 2 * part) {
+        int v = 0;
+        for (int spins = 0;; ++spins) {
+            v = __hip_atomic_load(&c[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (v != 0) break;
+            if (spins >= p.spin_limit) {
+                if (p.err) atomicExch(p.err, 1);
+                v = 1;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        atomicAdd(&before[tid & 1], v - 1);
+    }
+    __syncthreads();
+    int base_gt = before[0], base_eq = before[1];
+#pragma unroll
+    for (int w = 0; w < 16; ++w)
+        if (w < wave) { base_gt += wtot[0][w]; base_eq += wtot[1][w]; }
+    const int dest_run = base_gt + min(base_eq, need_eq);
+    if (full) range_emit<NIT, true>(p, q, u, N, w_lo, T, need_eq, dest_run, base_eq);
+    else range_emit<NIT, false>(p, q, u, N, w_lo, T, need_eq, dest_run, base_eq);
+}
+
 #define RF_CHECK_LAUNCH()                     \
     do {                                      \
         hipError_t e_ = hipGetLastError();    \
@@ -519,6 +688,20 @@ hipError_t select_topk(const SelParams &p, hipStream_t st)
         const long nz = max((long)p.nq * 3 * 2048, (long)p.zero_extra_n);
         hipLaunchKernelGGL(sel_zero, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, p);
         RF_CHECK_LAUNCH();
+        // one launch for the rest when the row's workgroups can all be resident together
+        if (p.multi_ok) {
+            for (int nit = 1; nit <= 8; nit *= 2) {
+                const long parts = (p.N + (long)nit * 4096 - 1) / ((long)nit * 4096);
+                if ((long)p.nq * parts > kMultiMaxGroups) continue;
+                const dim3 grid((unsigned)(p.nq * parts));
+                if (nit == 1) hipLaunchKernelGGL(select_multi<1>, grid, dim3(1024), 0, st, p, (int)parts);
+                else if (nit == 2) hipLaunchKernelGGL(select_multi<2>, grid, dim3(1024), 0, st, p, (int)parts);
+                else if (nit == 4) hipLaunchKernelGGL(select_multi<4>, grid, dim3(1024), 0, st, p, (int)parts);
+                else hipLaunchKernelGGL(select_multi<8>, grid, dim3(1024), 0, st, p, (int)parts);
+                RF_CHECK_LAUNCH();
+                return hipSuccess;
+            }
+        }
     }
     const dim3 sgrid(p.nblk, p.nq);
     const int hblk = max(1, kHistWorkgroups / p.nq);       // workgroups per row of the histogram passes

@@ -80,10 +80,14 @@ def test_matches_oracle(Hkv, d, n, B, dtype, ties):
     (2, 65537, 30000, 3, True, 0, 0),       # first size of the multi-launch selection
     (2, 70001, 30000, 3, True, 256, 256),
     (1, 131072, 1000, 0, False, 0, 0),
+    (8, 65536, 32768, 0, True, 0, 0),       # 16 workgroups per row in the one-launch selection of long rows
+    (3, 300000, 123456, 1, True, 7, 9),     # several candidates blocks per workgroup there, ragged
+    (33, 140001, 50000, 3, True, 0, 0),     # too many workgroups for one launch: the multi-launch selection
 ])
 def test_selection_paths(Hkv, n, B, pad, ties, sink, recent):
-    """Sizes on both sides of every switch inside the selection (registers per lane, one launch
-    against several), with ties, forced slots and rows that cannot be read as aligned quads."""
+    """Sizes on both sides of every switch inside the selection (registers per lane, one workgroup
+    per row, several workgroups per row in one launch, several launches), with ties, forced slots
+    and rows that cannot be read as aligned quads."""
     cap = n + pad
     run_case(Hkv, 64, n, B, cap, torch.bfloat16, rand_scores(Hkv, cap, n + B + pad, ties), sink, recent, seed=n)
 
