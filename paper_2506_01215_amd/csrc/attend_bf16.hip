@@ -18,6 +18,8 @@
 // C[m][n]: lane l holds n = l%16 and, in accumulator element e, m = 4*(l/16) + e).
 #include "common.h"
 
+#include <atomic>
+
 namespace reform {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -736,8 +738,16 @@ static hipError_t launch_fwd(AttnParams p, hipStream_t st)
     const int grid = p.Hkv * (p.G / gp) * p.n_row_blocks;
     const size_t smem = fwd_lds_bytes<D>();
     auto kern = attn_fwd_bf16<D>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    // the kernel needs more than the default 64 KB of LDS: raised once per device, not per launch
+    static std::atomic<bool> lds_raised[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !lds_raised[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) lds_raised[dev].store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, st, p);
     return hipGetLastError();
 }

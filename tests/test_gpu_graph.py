@@ -162,3 +162,78 @@ def test_two_streams_with_their_own_workspaces_do_not_interfere():
             for name in ("K", "V"):
                 assert torch.equal(b[name][:, :B], ref[name][:, :B]), (rep, name)
             assert torch.equal(b["score"][:, :B], ref["score"][:, :B]) and torch.equal(b["pos"][:, :B], ref["pos"][:, :B])
+
+
+def test_long_row_eviction_under_graph_replay_and_on_two_streams():
+    """Eviction at 65536 candidates per head uses several workgroups per row that wait for each
+    other inside one launch: captured and replayed on new scores, and issued on two streams at
+    once (2 x 128 workgroups fit on the chip together), it gives what the eager call gives, and
+    the device-side status word stays clear."""
+    Hkv, d, n, B = 8, 64, 65536, 32768
+    g = torch.Generator(device=DEV).manual_seed(41)
+    K0 = torch.randn((Hkv, n, d), generator=g, device=DEV).bfloat16()
+    V0 = torch.randn((Hkv, n, d), generator=g, device=DEV).bfloat16()
+    pos0 = torch.arange(n, dtype=torch.int32, device=DEV).repeat(Hkv, 1).contiguous()
+    scores = [torch.randint(0, 4096, (Hkv, n), generator=g, device=DEV).float() / 64.0 for _ in range(3)]   # many exact ties
+    nws = binding.evict_workspace_bytes(binding.evict_desc(K0, n, B, 4, 4)) + 512
+
+    def buffers():
+        return dict(K=torch.empty_like(K0), V=torch.empty_like(V0), pos=torch.empty_like(pos0),
+                    s_in=torch.empty_like(scores[0]), score=torch.empty_like(scores[0]),
+                    kept=torch.empty((Hkv, B), dtype=torch.int32, device=DEV),
+                    ws=torch.full((nws,), 0x5a, dtype=torch.uint8, device=DEV))
+
+    def step(b):
+        b["K"].copy_(K0)
+        b["V"].copy_(V0)
+        b["pos"].copy_(pos0)
+        b["score"].copy_(b["s_in"])
+        binding.reform_evict_topk_compact(b["K"], b["V"], b["score"], n, B, 4, 4, pos=b["pos"],
+                                          kept_idx=b["kept"], workspace=b["ws"])
+
+    def same(a, b):
+        assert torch.equal(a["kept"], b["kept"])
+        for name in ("K", "V", "score", "pos"):
+            assert torch.equal(a[name][:, :B], b[name][:, :B]), name
+        assert binding.evict_status_word(a["ws"]) == 0 and binding.evict_status_word(b["ws"]) == 0
+
+    eager, graphed = buffers(), buffers()
+    graphed["s_in"].copy_(scores[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(graphed)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(graphed)
+    for r, s in enumerate(scores):
+        print(f"[graph] long-row eviction replay {r}", flush=True)
+        eager["s_in"].copy_(s)
+        step(eager)
+        torch.cuda.synchronize()
+        graphed["s_in"].copy_(s)
+        graph.replay()
+        torch.cuda.synchronize()
+        same(eager, graphed)
+    # two streams at once, each with its own buffers and workspace
+    a, b = buffers(), buffers()
+    a["s_in"].copy_(scores[1])
+    b["s_in"].copy_(scores[2])
+    refs = []
+    for x, s in ((a, scores[1]), (b, scores[2])):
+        eager["s_in"].copy_(s)
+        step(eager)
+        torch.cuda.synchronize()
+        refs.append({k: v.clone() for k, v in eager.items()})
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        print(f"[graph] long-row eviction on two streams, round {rep}", flush=True)
+        torch.cuda.synchronize()
+        for x, st in zip((a, b), streams):
+            with torch.cuda.stream(st):
+                step(x)
+        torch.cuda.synchronize()
+        same(a, refs[0])
+        same(b, refs[1])
