@@ -120,6 +120,8 @@ def oracle_stream_pass(cfg, synth):
         K, V, _, _, _ = oracle.evict_compact(K, V, score, None, M + Ct, cfg.B)
         dt += time.perf_counter() - t0
         M = min(M + Ct, cfg.B)
+        if dt > 20.0:                       # a long pass says where it is (stderr; stdout stays one JSON line)
+            print(f"[bench] oracle pass of {cfg.name}: chunk {t + 1}/{cfg.n_chunks}, {dt:.0f} s", file=sys.stderr, flush=True)
     return dt
 
 

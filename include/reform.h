@@ -237,6 +237,10 @@ reform_status reform_gather_similarity(const reform_gather_desc *desc,
  *     pooled   [n_ctx] fp32 out, may be NULL (then it lives in the workspace only)
  * Supported: as reform_gather_topk; pool_window odd, 1 <= pool_window <= 1025;
  * n_head_keep + n_tail_keep <= budget <= n_ctx.
+ * Device-side status: the one row of pooled scores is selected, when it has more than 32768
+ * entries and at most 4 million, by up to 128 workgroups that wait for each other inside one
+ * launch, with the bounded wait described for reform_evict_topk_compact; the first int32 of the
+ * workspace is cleared by the call and set to 1 if such a wait expired (sel_idx is then undefined).
  */
 typedef struct {
     uint32_t struct_size;

@@ -187,6 +187,9 @@ __device__ __forceinline__ void sel_clear(const SelParams &p, long i0, long stri
     const long nh = (long)p.nq * 3 * 2048;
     for (long i = i0; i < nh; i += stride) p.hist[i] = 0;
     for (long i = i0; i < p.zero_extra_n; i += stride) p.zero_extra[i] = 0;
+    if (p.multi_ok)
+        for (long i = i0; i < (long)p.nq * p.nblk * 2; i += stride) p.blk_cnt[i] = 0;
+    if (p.err && i0 == 0) *p.err = 0;
 }
 
 // Exclusive scan of one int per thread over a 256-thread workgroup (tmp: 4 ints of LDS);

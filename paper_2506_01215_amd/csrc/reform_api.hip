@@ -151,7 +151,7 @@ reform_status check_pooled(const reform_pooled_desc *d)
 }
 
 struct PooledLayout {
-    size_t sim, pooled, hist, prefix, krem, blk, total;
+    size_t status, sim, pooled, hist, prefix, krem, blk, total;
     int nblk;
 };
 
@@ -160,6 +160,7 @@ PooledLayout pooled_layout(const reform_pooled_desc *d)
     PooledLayout L;
     L.nblk = (int)((d->n_ctx + 4095) / 4096);
     size_t off = 0;
+    L.status = off; off += align_up(sizeof(int));
     L.sim = off;    off += align_up((size_t)d->n_query * sim_pitch(d->n_ctx) * sizeof(float));
     L.pooled = off; off += align_up((size_t)d->n_ctx * sizeof(float));
     L.hist = off;   off += align_up((size_t)3 * 2048 * sizeof(int));
@@ -483,6 +484,9 @@ reform_status reform_gather_pooled(const reform_pooled_desc *d, const void *emb,
     p.sel.blk_cnt = (int *)(ws + L.blk);
     p.sel.nblk = L.nblk;
     p.sel.out_idx = sel_idx; p.sel.out_val = nullptr; p.sel.out_ld = d->budget;
+    p.sel.multi_ok = 1;
+    p.sel.err = (int *)(ws + L.status);
+    p.sel.spin_limit = g_move_spin_limit.load(std::memory_order_relaxed);
     return gather_pool_select(p, st) == hipSuccess ? REFORM_OK : REFORM_ERR_RUNTIME;
 }
 

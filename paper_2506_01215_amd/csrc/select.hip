@@ -13,7 +13,7 @@
 //   select_fused  rows of at most 32768 candidates: all of the above in one launch, one workgroup
 //                 per row, keys held in registers
 //   select_multi  longer rows, when every workgroup of the launch fits on the chip at once: one
-//                 launch, several workgroups per row that meet at four counted barriers
+//                 launch, several workgroups per row that wait for each other (keys in registers)
 // Candidates in the first n_sink or last n_recent slots get the maximal key (always selected).
 #include "common.h"
 
@@ -46,6 +46,7 @@ __global__ void sel_zero(SelParams p)
     if (i < (long)p.nq * 3 * 2048) p.hist[i] = 0;
     if (i < p.zero_extra_n) p.zero_extra[i] = 0;
     if (p.multi_ok && i < (long)p.nq * p.nblk * 2) p.blk_cnt[i] = 0;
+    if (p.err && i == 0) *p.err = 0;
 }
 
 __device__ __forceinline__ int digit_of(uint32_t u, int pass)
@@ -688,19 +689,19 @@ hipError_t select_topk(const SelParams &p, hipStream_t st)
         const long nz = max((long)p.nq * 3 * 2048, (long)p.zero_extra_n);
         hipLaunchKernelGGL(sel_zero, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, p);
         RF_CHECK_LAUNCH();
-        // one launch for the rest when the row's workgroups can all be resident together
-        if (p.multi_ok) {
-            for (int nit = 1; nit <= 8; nit *= 2) {
-                const long parts = (p.N + (long)nit * 4096 - 1) / ((long)nit * 4096);
-                if ((long)p.nq * parts > kMultiMaxGroups) continue;
-                const dim3 grid((unsigned)(p.nq * parts));
-                if (nit == 1) hipLaunchKernelGGL(select_multi<1>, grid, dim3(1024), 0, st, p, (int)parts);
-                else if (nit == 2) hipLaunchKernelGGL(select_multi<2>, grid, dim3(1024), 0, st, p, (int)parts);
-                else if (nit == 4) hipLaunchKernelGGL(select_multi<4>, grid, dim3(1024), 0, st, p, (int)parts);
-                else hipLaunchKernelGGL(select_multi<8>, grid, dim3(1024), 0, st, p, (int)parts);
-                RF_CHECK_LAUNCH();
-                return hipSuccess;
-            }
+    }
+    // one launch for the rest when the row's workgroups can all be resident together
+    if (p.multi_ok) {
+        for (int nit = 1; nit <= 8; nit *= 2) {
+            const long parts = (p.N + (long)nit * 4096 - 1) / ((long)nit * 4096);
+            if ((long)p.nq * parts > kMultiMaxGroups) continue;
+            const dim3 grid((unsigned)(p.nq * parts));
+            if (nit == 1) hipLaunchKernelGGL(select_multi<1>, grid, dim3(1024), 0, st, p, (int)parts);
+            else if (nit == 2) hipLaunchKernelGGL(select_multi<2>, grid, dim3(1024), 0, st, p, (int)parts);
+            else if (nit == 4) hipLaunchKernelGGL(select_multi<4>, grid, dim3(1024), 0, st, p, (int)parts);
+            else hipLaunchKernelGGL(select_multi<8>, grid, dim3(1024), 0, st, p, (int)parts);
+            RF_CHECK_LAUNCH();
+            return hipSuccess;
         }
     }
     const dim3 sgrid(p.nblk, p.nq);
