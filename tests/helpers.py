@@ -190,3 +190,39 @@ def oracle_kv_heads_dense(q, K, V, M, scale, kv_heads, threads=None):
             lse[hh[sel], ii[sel]] = l
             score += s[:, :n]
     return out, lse, score
+
+
+def build_store_gpu(raw, head_dim=128):
+    """The embedding store the GPU path makes of raw head states [N, D] (device tensor): one
+    reform_embed_save_selected call normalises the D/head_dim segments of every row."""
+    from paper_2506_01215_amd import binding
+    N, D = raw.shape
+    store = torch.empty_like(raw)
+    binding.reform_embed_save_selected(raw.view(N, D // head_dim, head_dim).permute(1, 0, 2), store, 0, 0)
+    return store
+
+
+def build_store_oracle(raw, head_dim=128, block=65536):
+    """The same store by the oracle's own routine (fp64, then rounded to the storage type), from
+    the same raw head states; returns a host tensor of raw's dtype."""
+    import oracle
+    N, D = raw.shape
+    out = torch.empty((N, D), dtype=raw.dtype)
+    for r0 in range(0, N, block):
+        r1 = min(N, r0 + block)
+        src = raw[r0:r1].float().cpu().numpy()
+        emb = np.zeros((r1 - r0, D), np.float64)
+        for h in range(D // head_dim):
+            oracle.embed_segment(src[:, h * head_dim:(h + 1) * head_dim], emb, h * head_dim)
+        out[r0:r1] = torch.from_numpy(emb).to(raw.dtype)
+    return out
+
+
+def stores_for(cfg, emb, qry):
+    """(GPU-side emb, qry on the device; oracle-side emb, qry on the host) for a gather workload:
+    the same tensors for kind "iid", each side's own embedding construction for "head_states"."""
+    dev = "cuda:0"
+    if cfg.kind == "head_states":
+        return (build_store_gpu(emb.to(dev)), build_store_gpu(qry.to(dev)),
+                build_store_oracle(emb), build_store_oracle(qry))
+    return emb.to(dev), qry.to(dev), emb.cpu(), qry.cpu()

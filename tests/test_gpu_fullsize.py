@@ -12,7 +12,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import assert_close, assert_scores_close, assert_selection_within_band, numpy_union, to_np
+from helpers import assert_close, assert_scores_close, assert_selection_within_band, numpy_union, stores_for, to_np
 from paper_2506_01215_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -152,12 +152,13 @@ def test_workload5_ragged_tail_exact():
 
 
 def check_gather_full(gcfg):
-    emb, qry = synth.gather_inputs(gcfg, DEV)
+    emb, qry, emb_o, qry_o = stores_for(gcfg, *synth.gather_inputs(gcfg, DEV))
     print(f"[fullsize] gather {gcfg.name}", flush=True)
     sim = binding.reform_gather_similarity(emb, qry)
     idx, sc, uni, cnt = binding.reform_gather_topk(emb, qry, gcfg.k, gcfg.radius)
     torch.cuda.synchronize()
-    sim_ref = oracle.cosine(to_np(emb), to_np(qry))
+    sim_ref = oracle.cosine(to_np(emb_o), to_np(qry_o))
+    del emb_o
     assert_close(sim.cpu().numpy(), sim_ref, 2e-2, "sim")
     idx_h = idx.cpu().numpy()
     subs = 0

@@ -4,14 +4,15 @@ import pytest
 import torch
 
 import oracle
-from helpers import RTOL, assert_close, assert_selection_within_band, numpy_union, to_np
+from helpers import RTOL, assert_close, assert_selection_within_band, numpy_union, stores_for, to_np
 from paper_2506_01215_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def run_case(emb, qry, k, radius=0, n_head=0, n_tail=0, expect_exact=False):
+def run_case(emb, qry, k, radius=0, n_head=0, n_tail=0, expect_exact=False, ref=None):
+    """ref: (emb, qry) as the oracle side sees them when each side builds its own store."""
     dtype = emb.dtype
     N, D = emb.shape
     nq = qry.shape[0]
@@ -20,7 +21,8 @@ def run_case(emb, qry, k, radius=0, n_head=0, n_tail=0, expect_exact=False):
     sim = binding.reform_gather_similarity(ed, qd)
     idx, sc, uni, cnt = binding.reform_gather_topk(ed, qd, k, radius, n_head, n_tail)
     torch.cuda.synchronize()
-    sim_ref, topk_ref, uni_ref = oracle.gather(to_np(emb), to_np(qry), k, radius, n_head, n_tail)
+    emb_o, qry_o = ref if ref is not None else (emb, qry)
+    sim_ref, topk_ref, uni_ref = oracle.gather(to_np(emb_o), to_np(qry_o), k, radius, n_head, n_tail)
     rtol = RTOL[dtype]
     assert_close(sim.cpu().numpy(), sim_ref, rtol, "sim")
     idx_h, sc_h = idx.cpu().numpy(), sc.cpu().numpy()
@@ -101,5 +103,5 @@ def test_zero_rows_hit_the_eps_clamp():
 
 def test_normalised_head_embeddings_small():
     cfg = synth.scaled(synth.GATHERS[4], N=20000, k=512)
-    emb, qry = synth.gather_inputs(cfg)
-    run_case(emb, qry, cfg.k, cfg.radius)
+    emb_d, qry_d, emb_o, qry_o = stores_for(cfg, *synth.gather_inputs(cfg))
+    run_case(emb_d, qry_d, cfg.k, cfg.radius, ref=(emb_o, qry_o))

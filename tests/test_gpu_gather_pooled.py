@@ -12,7 +12,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import RTOL, assert_close, assert_selection_within_band, to_np
+from helpers import RTOL, assert_close, assert_selection_within_band, stores_for, to_np
 from paper_2506_01215_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -28,13 +28,14 @@ def exact_on_own_scores(pooled, budget, n_head, n_tail):
     return np.sort(np.lexsort((np.arange(n), -key))[:budget])
 
 
-def check(emb, qry, budget, window, n_head, n_tail, rtol, label):
+def check(emb, qry, budget, window, n_head, n_tail, rtol, label, ref=None):
     print(f"[pooled] {label}: N={emb.shape[0]} D={emb.shape[1]} nq={qry.shape[0]} budget={budget} "
           f"window={window} keep={n_head}/{n_tail}", flush=True)
     sel, pooled = binding.reform_gather_pooled(emb, qry, budget, window, n_head, n_tail)
     torch.cuda.synchronize()
     sel_h, pooled_h = sel.cpu().numpy(), pooled.cpu().numpy()
-    _, p_ref, s_ref = oracle.gather_pooled(to_np(emb), to_np(qry), budget, window, n_head, n_tail)
+    emb_o, qry_o = ref if ref is not None else (emb, qry)
+    _, p_ref, s_ref = oracle.gather_pooled(to_np(emb_o), to_np(qry_o), budget, window, n_head, n_tail)
     assert_close(pooled_h, p_ref, rtol, f"{label}: pooled scores")
     np.testing.assert_array_equal(sel_h, exact_on_own_scores(pooled_h, budget, n_head, n_tail))
     n = emb.shape[0]
@@ -87,5 +88,5 @@ def test_bf16_workload4_full_size():
     """N = 1 048 576, D = 2048, 16 query tokens, budget 16384, window 129, 256 + 256 forced:
     the configuration bench.py times for this call."""
     gcfg = synth.GATHERS[4]
-    emb, qry = synth.gather_inputs(gcfg, DEV)
-    check(emb, qry, 16384, 129, 256, 256, RTOL[torch.bfloat16], "bf16 workload 4")
+    emb, qry, emb_o, qry_o = stores_for(gcfg, *synth.gather_inputs(gcfg, DEV))
+    check(emb, qry, 16384, 129, 256, 256, RTOL[torch.bfloat16], "bf16 workload 4", ref=(emb_o, qry_o))

@@ -50,7 +50,9 @@ def test_gather_inputs():
     cfg = synth.scaled(synth.GATHERS[4], N=300, n_query=3, k=16)
     emb, qry = synth.gather_inputs(cfg, block_rows=128)
     assert emb.shape == (300, 2048) and qry.shape == (3, 2048) and emb.dtype == torch.bfloat16
+    # raw head states: the per-head normalisation is the embedding-construction step's job, not the generator's
     seg = emb.float().view(300, 16, 128).norm(dim=-1)
-    assert torch.allclose(seg, torch.ones_like(seg), atol=2e-2)
+    assert (seg - 128 ** 0.5).abs().mean() < 1.0 and seg.std() > 0.3
+    assert synth.GATHERS[4].kind == "head_states"
     emb2, _ = synth.gather_inputs(cfg, block_rows=128)
     assert torch.equal(emb, emb2)
