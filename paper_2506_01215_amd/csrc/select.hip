@@ -17,6 +17,8 @@
 // Candidates in the first n_sink or last n_recent slots get the maximal key (always selected).
 #include "common.h"
 
+#include <atomic>
+
 namespace reform {
 
 constexpr int kSelBlock = 4096;      // candidates per selection workgroup (256 threads x 16)
@@ -675,6 +677,19 @@ __global__ __launch_bounds__(1024) void select_multi(SelParams p, int parts)
         if (e_ != hipSuccess) return e_;      \
     } while (0)
 
+// Compute units of the current device (cached per device; 256 on an unpartitioned MI355X).
+static int device_compute_units()
+{
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    int v = cached[dev].load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 0;
+    cached[dev].store(v, std::memory_order_relaxed);
+    return v;
+}
+
 hipError_t select_topk(const SelParams &p, hipStream_t st)
 {
     if (p.N <= kFusedMaxN) {
@@ -692,9 +707,11 @@ hipError_t select_topk(const SelParams &p, hipStream_t st)
     }
     // one launch for the rest when the row's workgroups can all be resident together
     if (p.multi_ok) {
+        // at most half of the compute units (a partitioned device has fewer than 256)
+        const long max_groups = min((long)kMultiMaxGroups, (long)device_compute_units() / 2);
         for (int nit = 1; nit <= 8; nit *= 2) {
             const long parts = (p.N + (long)nit * 4096 - 1) / ((long)nit * 4096);
-            if ((long)p.nq * parts > kMultiMaxGroups) continue;
+            if ((long)p.nq * parts > max_groups) continue;
             const dim3 grid((unsigned)(p.nq * parts));
             if (nit == 1) hipLaunchKernelGGL(select_multi<1>, grid, dim3(1024), 0, st, p, (int)parts);
             else if (nit == 2) hipLaunchKernelGGL(select_multi<2>, grid, dim3(1024), 0, st, p, (int)parts);

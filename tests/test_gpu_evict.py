@@ -83,6 +83,8 @@ def test_matches_oracle(Hkv, d, n, B, dtype, ties):
     (8, 65536, 32768, 0, True, 0, 0),       # 16 workgroups per row in the one-launch selection of long rows
     (3, 300000, 123456, 1, True, 7, 9),     # several candidates blocks per workgroup there, ragged
     (33, 140001, 50000, 3, True, 0, 0),     # too many workgroups for one launch: the multi-launch selection
+    (1, 600001, 250000, 1, True, 2, 2),     # 8192 keys per workgroup of the one-launch selection
+    (1, 3000000, 1000, 0, False, 0, 0),     # 32768 keys per workgroup, 92 workgroups for the one row
 ])
 def test_selection_paths(Hkv, n, B, pad, ties, sink, recent):
     """Sizes on both sides of every switch inside the selection (registers per lane, one workgroup
