@@ -35,6 +35,9 @@ __device__ __forceinline__ int sim_qrow(int D)   // LDS row pitch in elements: p
     return D + (((32 - rem) & 255) >> 1);
 }
 
+// FULL: dim is a multiple of 32 * kChunk, so every prefetch chunk is whole and the loads and MFMAs of
+// a loop trip are unconditional (the compiler can then count the loads in flight exactly).
+template <bool FULL>
 __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
 {
     extern __shared__ __attribute__((aligned(16))) u16 qs[];   // [16][QROW]
@@ -100,6 +103,18 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
     int l_ch = 0;
     const u16 *l_base = row_ptr(grp);
     auto load_next = [&](v4u (&dst)[kChunk]) {
+        if (FULL) {
+            // past the wave's last group the cursor stays on it: a few redundant loads instead of a branch
+#pragma unroll
+            for (int i = 0; i < kChunk; ++i) dst[i] = *(const v4u *)(l_base + (l_ch * kChunk + i) * 32);
+            if (l_grp < ngroups && ++l_ch == nchunks) {
+                const long g = next_grp(l_grp);
+                l_grp = g;
+                if (g < ngroups) { l_ch = 0; l_base = row_ptr(g); }
+                else l_ch = nchunks - 1;
+            }
+            return;
+        }
         if (l_grp >= ngroups) return;
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
@@ -123,7 +138,7 @@ __global__ __launch_bounds__(kSimThreads) void sim_bf16_mfma(GatherParams p)
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             const int ks = ch * kChunk + i;
-            if (ks < nks) {
+            if (FULL || ks < nks) {
                 const bf16x8 a = as_bf16x8(cur[i]);
                 const bf16x8 b = as_bf16x8(*(const v4u *)(qsrc + ks * 32));
                 dot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, dot, 0, 0, 0);
@@ -327,10 +342,10 @@ hipError_t gather_similarity(GatherParams p, int dtype_is_bf16, hipStream_t st)
             long grid = (ngroups + 7) / 8;
             const long cap = (long)cus * 2;
             if (grid > cap) grid = cap;
-            hipError_t e = hipFuncSetAttribute((const void *)sim_bf16_mfma,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            auto kern = p.D % (32 * kChunk) == 0 ? sim_bf16_mfma<true> : sim_bf16_mfma<false>;
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(sim_bf16_mfma, dim3((unsigned)grid), dim3(kSimThreads), smem, st, p);
+            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kSimThreads), smem, st, p);
         } else {
             const size_t smem = (size_t)p.nq_grp * p.D * sizeof(float);
             long grid = (p.N + 3) / 4;
